@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSM-layer prefill on one MI355X.
+
+A step is one pass of the whole hot path (plan reuse, one `ssm_prefill` call:
+decay prefix, masked scores, intra-chunk term, chunk states, state passing,
+checkpoint emission, fused output) over one batch of synthetic input that is
+already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def algorithmic_bytes(wl) -> int:
+    """Compulsory HBM bytes of one call: x and y once, dt, B, C once, every
+    non-null initial state read once, every checkpoint written once."""
+    s = wl.shape
+    esz = 4 if s.io_dtype == "f32" else 2
+    per_token = (2 * s.nheads * s.headdim + s.nheads + 2 * s.ngroups * s.d_state) * esz
+    state = s.nheads * s.headdim * s.d_state * 4
+    n_init = sum(1 for k in wl.init_kind if k != "zeros")
+    return wl.total_tokens * per_token + (n_init + wl.n_ckpt) * state
+
+
+def algorithmic_flops(wl, tile: int) -> float:
+    """Dense-tile flops of the chunked form with tiles of `tile` tokens, per
+    (token, head): masked scores 2*q*N shared by the heads of a group, intra
+    term 2*q*P, state update 2*P*N, state-times-C 2*P*N."""
+    s = wl.shape
+    per_th = 2 * tile * s.d_state * s.ngroups / s.nheads + 2 * tile * s.headdim + 4 * s.headdim * s.d_state
+    return float(wl.total_tokens) * s.nheads * per_th
+
+
+def cpu_baseline(wl, sample_tokens: int):
+    """The oracle as it stands on the host cores, on the first `sample_tokens`
+    tokens of the first sequence (all heads, zero initial state)."""
+    import oracle
+
+    n = min(sample_tokens, wl.seqlens[0])
+    inp = wl.inputs
+    x = inp.x[:n].float().cpu().numpy()
+    dt = inp.dt[:n].float().cpu().numpy()
+    B = inp.B[:n].float().cpu().numpy()
+    C = inp.C[:n].float().cpu().numpy()
+    A = wl.A.cpu().numpy()
+    D = wl.D.cpu().numpy()
+    threads = oracle.max_threads()
+    oracle.ssm_prefill_oracle(x[:16], dt[:16], A, B[:16], C[:16], D, [0, 16], None, [[16]])  # load + warm
+    t0 = time.perf_counter()
+    oracle.ssm_prefill_oracle(x, dt, A, B, C, D, [0, n], None, [[n]], nthreads=threads)
+    el = time.perf_counter() - t0
+    return {"value": n / el, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} tokens of the workload, all {wl.shape.nheads} heads, zero initial state, "
+                      f"one checkpoint; {el:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="named configuration 0..4 (default: the 7B 32K one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2411_19379_amd as ssm
+    from workloads import make_workload
+
+    ssm.load_library()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = make_workload(args.config, dev)
+    s = wl.shape
+    inp = wl.inputs
+
+    # Initial states: random fp32 ones come with the workload; a "prefix" one
+    # is the library's own state after scanning the random prefix from zero,
+    # i.e. the cache entry a previous request would have left behind.
+    init = list(wl.init_state)
+    if wl.prefix is not None:
+        pplan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype,
+                         [0, wl.prefix_len], [[wl.prefix_len]])
+        _, pst = ssm.prefill(pplan, wl.prefix.x, wl.prefix.dt, wl.A, wl.prefix.B, wl.prefix.C, wl.D)
+        torch.cuda.synchronize()
+        pplan.close()
+        init = [pst[0].contiguous()]
+        wl.prefix = None
+    if all(v is None for v in init):
+        init = None
+
+    t0 = time.perf_counter()
+    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    y = torch.empty_like(inp.x)
+    st = torch.empty((max(wl.n_ckpt, 1), s.nheads, s.headdim, s.d_state), dtype=torch.float32, device=dev)
+
+    def step():
+        ssm.prefill(plan, inp.x, inp.dt, wl.A, inp.B, inp.C, wl.D, init, y_out=y, state_out=st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events on the stream the kernels are launched on (torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+    T = wl.total_tokens
+
+    abytes = algorithmic_bytes(wl)
+    achieved = abytes / (kern_ms * 1e-3) / 1e9
+    flops = algorithmic_flops(wl, plan.info.tile_tokens)
+    out = {
+        "metric": "SSM-layer prefill tokens/s (1 GPU) with state checkpoints",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if s.io_dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "tokens": T, "batch": wl.batch, "nheads": s.nheads,
+                   "headdim": s.headdim, "d_state": s.d_state, "ngroups": s.ngroups, "chunk": s.chunk,
+                   "checkpoints": wl.n_ckpt,
+                   "initial_states": 0 if init is None else sum(1 for v in init if v is not None),
+                   "kernel_path": "mfma_bf16" if plan.info.path == 1 else "valu_f32",
+                   "workgroups": plan.info.n_workgroups, "plan_ms": plan_ms},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "ssm_scan_mfma_kernel" if plan.info.path == 1 else "ssm_scan_valu_kernel",
+                     "kernel_ms": kern_ms, "algorithmic_bytes": abytes,
+                     "mfma_tflops_dense_tile": flops / (kern_ms * 1e-3) / 1e12,
+                     "mfma_frac": flops / (kern_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_tokens)
+    plan.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,157 @@
+/*
+ * ssm_prefill.h -- C ABI of the MI355X (gfx950) SSM-layer prefill library.
+ *
+ * One call scans a packed batch of variable-length requests through one
+ * Mamba2-style SSM layer.  Each request may start from a cached recurrent
+ * state (a prefix-cache hit) and may ask for the full fp32 state after any
+ * of its tokens (the checkpoints that become cache entries).
+ *
+ * Per head h, channel p, state index n and sequence-local token t = 1..len:
+ *
+ *     a_t      = exp(dt[t,h] * A[h])
+ *     S_t[p,n] = a_t * S_{t-1}[p,n] + dt[t,h] * x[t,h,p] * B[t,g(h),n]
+ *     y[t,h,p] = sum_n C[t,g(h),n] * S_t[p,n] + D[h] * x[t,h,p]
+ *
+ * with g(h) = h / (nheads / ngroups) and S_0 the request's initial state.
+ * (Paper Section 2.1 and Section 3: the state is a constant-size summary that
+ * every token overwrites in place.  Section 2.2: on a cache hit the prefix
+ * state is fetched before prefill.  Section 4.1, "Obtaining states during
+ * prefill": states are materialised during a chunked prefill, optionally at
+ * the exact token; a two-pass prefill resumes from the prefix state.)
+ *
+ * All tensors are row-major with the last index fastest.  "device" pointers
+ * are HIP device pointers on the current device; "host" pointers are ordinary
+ * process memory.  Every entry point returns SSM_OK (0) or a negative
+ * ssm_status_t; on error nothing has been enqueued and ssm_last_error()
+ * returns a message for the calling thread.  Nothing here throws or aborts.
+ */
+#ifndef SSM_PREFILL_H
+#define SSM_PREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SSM_OK = 0,
+    SSM_ERR_INVALID_ARG = -1,       /* NULL where a pointer is required, bad sizes      */
+    SSM_ERR_BAD_CU_SEQLENS = -2,    /* cu_seqlens[0] != 0 or decreasing                 */
+    SSM_ERR_BAD_CHECKPOINT = -3,    /* position outside 1..len, duplicate or unsorted   */
+    SSM_ERR_UNSUPPORTED_SHAPE = -4, /* shape outside what the kernels handle            */
+    SSM_ERR_WORKSPACE_TOO_SMALL = -5,
+    SSM_ERR_MISALIGNED = -6,        /* a device pointer is not 16-byte aligned          */
+    SSM_ERR_HIP = -7                /* a HIP runtime call failed                        */
+} ssm_status_t;
+
+typedef enum { SSM_DT_F32 = 0, SSM_DT_BF16 = 1 } ssm_dtype_t; /* type of x, dt, B, C, y */
+
+typedef struct {
+    int32_t nheads;    /* H */
+    int32_t headdim;   /* P */
+    int32_t d_state;   /* N */
+    int32_t ngroups;   /* G, divides H; heads of a group are contiguous */
+    int32_t chunk;     /* Q: tokens per chunk of the chunked scan (Section 4.1); a tuning
+                          knob that changes rounding order only, never which state is
+                          returned.  16 <= Q <= 256, multiple of 16. */
+    int32_t io_dtype;  /* ssm_dtype_t */
+} ssm_shape_t;
+
+typedef struct ssm_plan ssm_plan_t; /* opaque; owned by the library */
+
+/* Which kernel family a plan selected (ssm_plan_info). */
+enum { SSM_PATH_VALU_F32 = 0, SSM_PATH_MFMA_BF16 = 1 };
+
+typedef struct {
+    int32_t batch;
+    int32_t n_ckpt;        /* total checkpoints = number of fp32 [H,P,N] slots in state_out */
+    int64_t total_tokens;  /* T = cu_seqlens[batch] */
+    int32_t n_tiles;       /* token tiles the kernels walk (sequence-local, split at checkpoints) */
+    int32_t tile_tokens;   /* upper bound of a tile's length */
+    int32_t path;          /* SSM_PATH_* */
+    int32_t n_workgroups;  /* grid size of the scan kernel */
+} ssm_plan_info_t;
+
+/*
+ * Build the host-side plan for one packed batch: validate the request mix and
+ * cut every sequence into tiles.  Tiles never cross a sequence boundary and
+ * always end at each requested checkpoint position, so a checkpoint is the
+ * scan's running state at a tile end (exact position, Section 4.1).  Host
+ * only: touches no GPU.  A plan can be reused for every SSM layer of the
+ * batch (24 layers in the paper's 7B hybrid, Section 5.1).
+ *
+ *   cu_seqlens_host [batch+1]  host; [0] == 0, non-decreasing; len 0 allowed
+ *   cu_ckpt_host    [batch+1]  host; CSR offsets into ckpt_pos_host; may be
+ *                              NULL when no checkpoint is requested at all
+ *   ckpt_pos_host              host; per sequence strictly ascending token
+ *                              COUNTS p, 1 <= p <= len: slot k receives the
+ *                              state after exactly p tokens of its sequence
+ *   out                        receives the plan; free with ssm_plan_destroy
+ */
+int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
+                    const int32_t *cu_seqlens_host,
+                    const int32_t *cu_ckpt_host,
+                    const int32_t *ckpt_pos_host,
+                    ssm_plan_t **out);
+
+/* Copy the plan's summary into *info. */
+int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info);
+
+/* Read tile i (0 <= i < n_tiles) of the plan: first packed token, length,
+ * owning sequence, and the checkpoint slot filled at its end (-1: none). */
+int ssm_plan_tile(const ssm_plan_t *plan, int32_t i, int32_t *tok0, int32_t *len,
+                  int32_t *seq, int32_t *ckpt_slot);
+
+/* Bytes of device workspace ssm_prefill needs for this plan (may be 0). The
+ * caller allocates it, 256-byte aligned, and may reuse it between calls. */
+int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes);
+
+/*
+ * Enqueue the scan of one SSM layer on `hip_stream` (a hipStream_t, NULL =
+ * the default stream).  Never synchronises the stream.  The first call with a
+ * plan uploads the plan's tile table (one small device allocation owned by
+ * the plan and a blocking copy); later calls only enqueue.  A plan must not
+ * be used by calls that overlap on different streams.
+ *
+ *   x      [T,H,P]  io_dtype  device  read only
+ *   dt     [T,H]    io_dtype  device  read only; final step sizes, positive
+ *                                     (no softplus, bias or clamp is applied)
+ *   A      [H]      fp32      device  read only; negative decay rates
+ *   B, C   [T,G,N]  io_dtype  device  read only
+ *   D      [H]      fp32      device  read only; skip weight per head
+ *   init_state_ptrs [batch]   HOST array of DEVICE pointers to fp32 [H,P,N];
+ *                             the array or any entry may be NULL (zero state).
+ *                             The states are read only: they are live cache
+ *                             entries.  The array is copied before return.
+ *   y_out  [T,H,P]  io_dtype  device  written
+ *   state_out [n_ckpt,H,P,N] fp32 device written; slot order = sequence
+ *                             major, then ascending position (CSR order); a
+ *                             slot may be passed back as an initial state of
+ *                             a later call unchanged.  May be NULL if n_ckpt
+ *                             is 0.
+ *   workspace       device, >= ssm_plan_workspace_bytes; may be NULL if 0
+ *
+ * Device pointers must be 16-byte aligned.  T == 0 succeeds and enqueues
+ * nothing.
+ */
+int ssm_prefill(ssm_plan_t *plan,
+                const void *x, const void *dt, const float *A,
+                const void *B, const void *C, const float *D,
+                const float *const *init_state_ptrs,
+                void *y_out, float *state_out,
+                void *workspace, size_t workspace_bytes,
+                void *hip_stream);
+
+/* Release the plan and its device table.  NULL is accepted. */
+void ssm_plan_destroy(ssm_plan_t *plan);
+
+/* Message of the last error on the calling thread ("" if none). The pointer
+ * stays valid until the next failing call on this thread. */
+const char *ssm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSM_PREFILL_H */

@@ -1,0 +1,208 @@
+// Host side of the library: argument validation and the tile table.
+// Nothing in this file touches the GPU.
+#include "plan.h"
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+static thread_local std::string g_last_error;
+
+void ssm_set_error(const std::string &msg) { g_last_error = msg; }
+
+extern "C" const char *ssm_last_error(void) { return g_last_error.c_str(); }
+
+static int fail(int code, const std::string &msg)
+{
+    ssm_set_error(msg);
+    return code;
+}
+
+// LDS bytes of the fp32 VALU kernel for a given shape (must mirror the
+// kernel's carve-up: state copy with padded rows, x/B/C tiles, score tile).
+size_t ssm_valu_lds_bytes(int P, int N)
+{
+    const size_t q = kValuTileTokens;
+    size_t floats = (size_t)P * (N + 1)   // state copy, rows padded by one float
+                    + q * P               // x tile
+                    + 2 * q * N           // B and C tiles
+                    + q * q               // masked score tile
+                    + 3 * q;              // dt, decay factors
+    return floats * sizeof(float) + q * sizeof(double);
+}
+
+static int choose_path(const ssm_shape_t &s, ssm_plan *plan)
+{
+    const int P = s.headdim, N = s.d_state;
+    if (s.io_dtype == SSM_DT_BF16 && N == 128 && P % 32 == 0 && P <= 256) {
+        plan->path = SSM_PATH_MFMA_BF16;
+        plan->p_split = P / 32;
+        plan->tile_tokens = s.chunk < kMfmaTileTokens ? s.chunk : kMfmaTileTokens;
+        return SSM_OK;
+    }
+    if ((size_t)P * N > 256u * 32u)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE,
+                    "headdim*d_state above 8192 is only supported for bf16 I/O with d_state 128");
+    if (ssm_valu_lds_bytes(P, N) > 64 * 1024)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE, "shape needs more than 64 KiB of LDS in the fp32 kernel");
+    plan->path = SSM_PATH_VALU_F32;
+    plan->p_split = 1;
+    plan->tile_tokens = kValuTileTokens;
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
+                               const int32_t *cu_seqlens_host,
+                               const int32_t *cu_ckpt_host,
+                               const int32_t *ckpt_pos_host,
+                               ssm_plan_t **out)
+{
+    if (!out)
+        return fail(SSM_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!shape)
+        return fail(SSM_ERR_INVALID_ARG, "shape is NULL");
+    if (batch < 0)
+        return fail(SSM_ERR_INVALID_ARG, "batch is negative");
+    if (!cu_seqlens_host)
+        return fail(SSM_ERR_INVALID_ARG, "cu_seqlens is NULL");
+    const ssm_shape_t &s = *shape;
+    if (s.nheads <= 0 || s.headdim <= 0 || s.d_state <= 0 || s.ngroups <= 0)
+        return fail(SSM_ERR_INVALID_ARG, "nheads, headdim, d_state and ngroups must be positive");
+    if (s.nheads % s.ngroups != 0)
+        return fail(SSM_ERR_INVALID_ARG, "ngroups must divide nheads");
+    if (s.io_dtype != SSM_DT_F32 && s.io_dtype != SSM_DT_BF16)
+        return fail(SSM_ERR_INVALID_ARG, "io_dtype must be SSM_DT_F32 or SSM_DT_BF16");
+    if (s.chunk < 16 || s.chunk > 256 || s.chunk % 16 != 0)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE, "chunk must be a multiple of 16 in 16..256");
+    if (s.nheads > 65535)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE, "nheads above 65535");
+    // 16-byte alignment of every token row of x/y, B/C and of a head's state
+    const int esz = s.io_dtype == SSM_DT_F32 ? 4 : 2;
+    if ((s.headdim * esz) % 16 != 0 || (s.d_state * esz) % 16 != 0)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE,
+                    "headdim and d_state rows must be multiples of 16 bytes");
+
+    if (cu_seqlens_host[0] != 0)
+        return fail(SSM_ERR_BAD_CU_SEQLENS, "cu_seqlens[0] must be 0");
+    for (int32_t i = 0; i < batch; ++i)
+        if (cu_seqlens_host[i + 1] < cu_seqlens_host[i])
+            return fail(SSM_ERR_BAD_CU_SEQLENS, "cu_seqlens must be non-decreasing");
+
+    int32_t n_ckpt = 0;
+    if (cu_ckpt_host) {
+        if (cu_ckpt_host[0] != 0)
+            return fail(SSM_ERR_BAD_CHECKPOINT, "cu_ckpt[0] must be 0");
+        for (int32_t i = 0; i < batch; ++i)
+            if (cu_ckpt_host[i + 1] < cu_ckpt_host[i])
+                return fail(SSM_ERR_BAD_CHECKPOINT, "cu_ckpt must be non-decreasing");
+        n_ckpt = cu_ckpt_host[batch];
+        if (n_ckpt > 0 && !ckpt_pos_host)
+            return fail(SSM_ERR_INVALID_ARG, "ckpt_pos is NULL but checkpoints are requested");
+        for (int32_t i = 0; i < batch; ++i) {
+            const int64_t len = (int64_t)cu_seqlens_host[i + 1] - cu_seqlens_host[i];
+            for (int32_t k = cu_ckpt_host[i]; k < cu_ckpt_host[i + 1]; ++k) {
+                const int32_t p = ckpt_pos_host[k];
+                if (p < 1 || p > len) {
+                    char buf[160];
+                    snprintf(buf, sizeof buf,
+                             "checkpoint %d of sequence %d is at %d, outside 1..%lld", k, i, p,
+                             (long long)len);
+                    return fail(SSM_ERR_BAD_CHECKPOINT, buf);
+                }
+                if (k > cu_ckpt_host[i] && p <= ckpt_pos_host[k - 1])
+                    return fail(SSM_ERR_BAD_CHECKPOINT,
+                                "checkpoint positions must be strictly ascending per sequence");
+            }
+        }
+    }
+
+    ssm_plan *plan = new (std::nothrow) ssm_plan();
+    if (!plan)
+        return fail(SSM_ERR_INVALID_ARG, "out of host memory");
+    plan->shape = s;
+    plan->batch = batch;
+    plan->n_ckpt = n_ckpt;
+    plan->total_tokens = cu_seqlens_host[batch];
+    int rc = choose_path(s, plan);
+    if (rc != SSM_OK) {
+        delete plan;
+        return rc;
+    }
+
+    // Cut each sequence into tiles.  Every stretch between two consecutive cut
+    // points (sequence start, each checkpoint, sequence end) is tiled from its
+    // own start, so a checkpoint is always the state at a tile end.
+    const int32_t q = plan->tile_tokens;
+    plan->seqs.resize(batch);
+    for (int32_t i = 0; i < batch; ++i) {
+        const int32_t t0 = cu_seqlens_host[i];
+        const int32_t len = cu_seqlens_host[i + 1] - t0;
+        plan->seqs[i].tile_begin = (int32_t)plan->tiles.size();
+        int32_t pos = 0;
+        int32_t k = cu_ckpt_host ? cu_ckpt_host[i] : 0;
+        const int32_t k_end = cu_ckpt_host ? cu_ckpt_host[i + 1] : 0;
+        while (pos < len) {
+            const int32_t stop = k < k_end ? ckpt_pos_host[k] : len;  // next cut point
+            while (pos < stop) {
+                SsmTile t;
+                t.tok0 = t0 + pos;
+                t.len = stop - pos < q ? stop - pos : q;
+                t.seq = i;
+                pos += t.len;
+                t.ckpt_slot = (pos == stop && k < k_end) ? k : -1;
+                plan->tiles.push_back(t);
+            }
+            if (k < k_end)
+                ++k;
+        }
+        plan->seqs[i].tile_end = (int32_t)plan->tiles.size();
+    }
+    const int64_t wgs = (int64_t)batch * s.nheads * plan->p_split;
+    if (wgs > 0x7fffffffLL) {
+        delete plan;
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE, "batch*nheads too large for one launch");
+    }
+    plan->n_workgroups = (int32_t)wgs;
+    *out = plan;
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info)
+{
+    if (!plan || !info)
+        return fail(SSM_ERR_INVALID_ARG, "plan or info is NULL");
+    info->batch = plan->batch;
+    info->n_ckpt = plan->n_ckpt;
+    info->total_tokens = plan->total_tokens;
+    info->n_tiles = (int32_t)plan->tiles.size();
+    info->tile_tokens = plan->tile_tokens;
+    info->path = plan->path;
+    info->n_workgroups = plan->n_workgroups;
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_tile(const ssm_plan_t *plan, int32_t i, int32_t *tok0, int32_t *len,
+                             int32_t *seq, int32_t *ckpt_slot)
+{
+    if (!plan)
+        return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
+    if (i < 0 || (size_t)i >= plan->tiles.size())
+        return fail(SSM_ERR_INVALID_ARG, "tile index out of range");
+    const SsmTile &t = plan->tiles[i];
+    if (tok0) *tok0 = t.tok0;
+    if (len) *len = t.len;
+    if (seq) *seq = t.seq;
+    if (ckpt_slot) *ckpt_slot = t.ckpt_slot;
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes)
+{
+    if (!plan || !bytes)
+        return fail(SSM_ERR_INVALID_ARG, "plan or bytes is NULL");
+    // The scan carries every sequence's state in registers from its first to
+    // its last token, so no intermediate state goes through device memory.
+    *bytes = 0;
+    return SSM_OK;
+}

@@ -1,0 +1,48 @@
+// Internal layout of a scan plan (host side) and of the tables the kernels read.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "ssm_prefill.h"
+
+// One token tile: a run of consecutive tokens of one sequence that the scan
+// kernel consumes in one step.  16 bytes, read by the kernels as an int4.
+struct SsmTile {
+    int32_t tok0;       // first token, index into the packed batch
+    int32_t len;        // 1 .. tile_tokens
+    int32_t ckpt_slot;  // state_out slot written after this tile, or -1
+    int32_t seq;        // owning sequence
+};
+
+// Per sequence: its tiles are [tile_begin, tile_end) of the tile table.
+struct SsmSeq {
+    int32_t tile_begin;
+    int32_t tile_end;
+};
+
+struct ssm_plan {
+    ssm_shape_t shape;
+    int32_t batch = 0;
+    int32_t n_ckpt = 0;
+    int64_t total_tokens = 0;
+    int32_t tile_tokens = 0;
+    int32_t path = SSM_PATH_VALU_F32;
+    int32_t p_split = 1;          // workgroups per (sequence, head): headdim is cut in p_split parts
+    int32_t n_workgroups = 0;
+    std::vector<SsmTile> tiles;
+    std::vector<SsmSeq> seqs;
+    // device copies, made by the first ssm_prefill call
+    int device = -1;
+    void *d_tiles = nullptr;      // SsmTile[n_tiles]
+    void *d_seqs = nullptr;       // SsmSeq[batch]
+    void *d_init_ptrs = nullptr;  // const float*[batch], refreshed by every call
+};
+
+void ssm_set_error(const std::string &msg);
+
+// Tile lengths the two kernel families work with.
+constexpr int kValuTileTokens = 16;
+constexpr int kMfmaTileTokens = 64;
