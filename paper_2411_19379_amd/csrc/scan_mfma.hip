@@ -26,6 +26,12 @@
 // transpose reads of gfx950.
 #include "device_utils.h"
 
+// Optional cycle-trace hooks for profiling builds; they expand to nothing here.
+#ifndef SSM_TRACE
+#define SSM_TRACE(slot)
+#define SSM_TRACE_DECL
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -90,19 +96,60 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also
+// wait for every outstanding global load, i.e. for the prefetch of the next
+// tile, on each of the two barriers of a tile.  Global memory written by this
+// kernel is never read back by it, so LDS ordering is all the stages need.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and the
+// two row broadcasts (no LDS round trips).
+#define SSM_DPP(old, v, ctrl, row_mask, bound)                                                      \
+    __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, (float)(old)),     \
+                                                          __builtin_bit_cast(int, (float)(v)), (ctrl), \
+                                                          (row_mask), 0xF, (bound)))
+__device__ __forceinline__ float wave_inclusive_sum(float v)
+{
+    v += SSM_DPP(0.f, v, 0x111, 0xF, true);  // row_shr:1
+    v += SSM_DPP(0.f, v, 0x112, 0xF, true);  // row_shr:2
+    v += SSM_DPP(0.f, v, 0x114, 0xF, true);  // row_shr:4
+    v += SSM_DPP(0.f, v, 0x118, 0xF, true);  // row_shr:8
+    v += SSM_DPP(0.f, v, 0x142, 0xA, false); // row_bcast:15 into rows 1 and 3
+    v += SSM_DPP(0.f, v, 0x143, 0xC, false); // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+__device__ __forceinline__ float read_lane(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 struct TileRegs {
     uint4 x;     // 8 channels of one token
     uint4 b[4];  // 4 x (one token row, 8 state indices) of B
     uint4 c[4];
-    float dt;    // lane j of every front wave: dt of token j
+    uint32_t dt; // lane j of every front wave: bf16 bits of dt of token j
 };
 
-// score blocks (16x16, jb <= ib) per front wave
-__constant__ const int8_t kScoreJb[4][3] = {{0, 0, 0}, {0, 1, 2}, {1, 1, 0}, {2, 3, 0}};
-__constant__ const int8_t kScoreIb[4][3] = {{0, 1, 2}, {3, 3, 3}, {1, 2, 0}, {2, 3, 0}};
-__constant__ const int8_t kScoreCnt[4] = {3, 3, 2, 2};
+// Score blocks (16x16, jb <= ib) of each front wave, one byte per block: jb in
+// the low nibble, ib in the high one.  Waves 0 and 1 take three blocks, waves 2
+// and 3 two; immediates rather than a table so that no memory read is needed.
+__device__ __forceinline__ uint32_t score_blocks(int w)
+{
+    return w == 0 ? 0x201000u : w == 1 ? 0x323130u : w == 2 ? 0x2111u : 0x3322u;
+}
 
-__global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int wg_per_xcd, int n_wg)
+// Pointers are separate __restrict__ parameters (not a struct) so that the
+// compiler may read the read-only tables with scalar loads.
+__global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A_,
+    const bf16_t *__restrict__ Bg, const bf16_t *__restrict__ Cg, const float *__restrict__ D_,
+    bf16_t *__restrict__ y, float *__restrict__ state_out, const float *const *__restrict__ init_ptrs,
+    const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P, int G, int p_split,
+    int wg_per_xcd, int n_wg)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     Lds &L = *reinterpret_cast<Lds *>(lds_raw);
@@ -117,20 +164,13 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
     const int lane = tid & 63;
     const int w = tid >> 6;
     const bool front = w < 4;
-    const int H = a.H, P = a.P, G = a.G;
-    const int ps = wg % a.p_split;
-    const int h = (wg / a.p_split) % H;
-    const int seq = wg / (a.p_split * H);
+    const int ps = wg % p_split;
+    const int h = (wg / p_split) % H;
+    const int seq = wg / (p_split * H);
     const int g = h / (H / G);
     const int pbase = ps * kPW;
-
-    const bf16_t *x = static_cast<const bf16_t *>(a.x);
-    const bf16_t *dt = static_cast<const bf16_t *>(a.dt);
-    const bf16_t *Bg = static_cast<const bf16_t *>(a.B);
-    const bf16_t *Cg = static_cast<const bf16_t *>(a.C);
-    bf16_t *y = static_cast<bf16_t *>(a.y);
-    const float Ah = a.A[h];
-    const float Dh = a.D[h];
+    const float Ah = A_[h];
+    const float Dh = D_[h];
 
     // front waves: staging roles (ft = 0..255)
     const int ft = tid & 255;
@@ -143,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
 
     f32x16 S = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (!front) {
-        const float *init = a.init_ptrs ? a.init_ptrs[seq] : nullptr;
+        const float *init = init_ptrs ? init_ptrs[seq] : nullptr;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -166,8 +206,10 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
         }
     }
 
-    const SsmSeq sq = a.seqs[seq];
+    const SsmSeq sq = seqs[seq];
     const int n_tiles = sq.tile_end - sq.tile_begin;
+    if (n_tiles <= 0)
+        return;  // empty sequence: the whole workgroup leaves before any barrier
 
     auto load_tile = [&](const SsmTile &t, TileRegs &r) {
         const size_t tok0 = (size_t)t.tok0;
@@ -188,37 +230,43 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
                 r.c[k] = *reinterpret_cast<const uint4 *>(Cg + off);
             }
         }
-        r.dt = 0.f;
+        r.dt = 0u;  // converted where it is used, so that nothing here waits for the loads
         if (lane < t.len)
-            r.dt = bf16_to_f32(dt[(tok0 + lane) * H + h]);
+            r.dt = dt[(tok0 + lane) * H + h];
     };
 
+    // Tile descriptors travel through a short register pipeline (tile s-1, s,
+    // s+1, and s+2 in flight), read with scalar loads two steps ahead of use.
+    // (Indices past the end are clamped: those descriptors are never used.)
+    auto tile_at = [&](int k) -> SsmTile {
+        const int kk = k < n_tiles ? k : n_tiles - 1;
+        return tiles[__builtin_amdgcn_readfirstlane(sq.tile_begin + kk)];
+    };
+    SsmTile tb = tile_at(0);      // tile s-1 (back waves; unused in step 0)
+    SsmTile t_cur = tile_at(0);   // tile s
+    SsmTile t_nxt = tile_at(1);   // tile s+1
+
     TileRegs R;
-    if (front && n_tiles > 0)
-        load_tile(a.tiles[sq.tile_begin], R);
+    if (front)
+        load_tile(t_cur, R);
     __syncthreads();
+    SSM_TRACE_DECL
 
     for (int s = 0; s <= n_tiles; ++s) {
         TileBuf &Tf = L.buf[s & 1];        // tile s, produced by the front waves
         TileBuf &Tb = L.buf[(s & 1) ^ 1];  // tile s-1, consumed by the back waves
-        SsmTile tb = {0, 0, -1, 0};
-        if (!front && s >= 1)
-            tb = a.tiles[sq.tile_begin + s - 1];
+        const SsmTile t_nn = tile_at(s + 2);
 
         // ================= phase 1 =================
         if (front) {
             if (s < n_tiles) {
                 // decay exponents: inclusive scan of dt*A over the 64 lanes (lane = token)
-                float ell = R.dt * Ah;
-#pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const float up = __shfl_up(ell, d, 64);
-                    if (lane >= d)
-                        ell += up;
-                }
+                const float dtj = __uint_as_float(R.dt << 16);
+                const float ell = wave_inclusive_sum(dtj * Ah);
+                SSM_TRACE(5);
                 const float ell2 = ell * kLog2e;
-                const float ell2_last = __shfl(ell2, 63, 64);
-                const float wj = exp2_fast(ell2_last - ell2) * R.dt;  // weight of token `lane` in the state update
+                const float ell2_last = read_lane(ell2, 63);
+                const float wj = exp2_fast(ell2_last - ell2) * dtj;  // weight of token `lane` in the state update
                 const float w_tok = __shfl(wj, x_tok, 64);
 
                 // x tile: raw copy and decay-weighted copy, both token major
@@ -243,15 +291,16 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
                 // per-token factors, spread over the four front waves
                 if (w == 0) {
                     L.ell2[lane] = ell2;
-                    L.cj[lane] = ell2 - __builtin_amdgcn_logf(R.dt);
+                    L.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
                     Tf.ei[lane] = exp2_fast(ell2);
                 } else {
-                    const float ref = __shfl(ell2, 16 * w - 1, 64);  // end of row block w-1
-                    L.cfac[w - 1][lane] = lane < 16 * w ? exp2_fast(ref - ell2) * R.dt : 0.f;
+                    const float ref = read_lane(ell2, 16 * w - 1);  // end of row block w-1
+                    L.cfac[w - 1][lane] = lane < 16 * w ? exp2_fast(ref - ell2) * dtj : 0.f;
                 }
+                SSM_TRACE(6);
                 // next tile's global loads fly while this one is turned into scores
                 if (s + 1 < n_tiles)
-                    load_tile(a.tiles[sq.tile_begin + s + 1], R);
+                    load_tile(t_nxt, R);
             }
         } else if (s >= 1) {
             // ---- outputs of tile s-1: Y^T[p, i], tokens i = 16kw + lane%16, two 16-channel blocks ----
@@ -293,15 +342,18 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
                 }
             }
         }
-        __syncthreads();
+        SSM_TRACE(1);
+        lds_barrier();
+        SSM_TRACE(2);
 
         // ================= phase 2 =================
         if (front) {
             if (s < n_tiles) {
                 // ---- Gm^T = mask(B C^T o decay): 16x16 blocks (jb <= ib), 2-3 per wave ----
-                const int cnt = kScoreCnt[w];
+                const int cnt = w < 2 ? 3 : 2;
+                const uint32_t blocks = score_blocks(w);
                 for (int t = 0; t < cnt; ++t) {
-                    const int jb = kScoreJb[w][t], ib = kScoreIb[w][t];
+                    const int jb = (blocks >> (8 * t)) & 3, ib = (blocks >> (8 * t + 4)) & 3;
                     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                     const bf16_t *pa = &Tf.Bs[16 * jb + (lane & 15)][8 * (lane >> 4)];
                     const bf16_t *pb = &Tf.Cs[16 * ib + (lane & 15)][8 * (lane >> 4)];
@@ -352,12 +404,17 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(ScanArgs a, int
                 *reinterpret_cast<uint2 *>(&L.Ss[s_p][n0]) =
                     make_uint2(pack2(S[4 * q4], S[4 * q4 + 1]), pack2(S[4 * q4 + 2], S[4 * q4 + 3]));
                 if (tb.ckpt_slot >= 0)
-                    *reinterpret_cast<float4 *>(a.state_out +
+                    *reinterpret_cast<float4 *>(state_out +
                                                 (((size_t)tb.ckpt_slot * H + h) * P + pbase + s_p) * kN + n0) =
                         make_float4(S[4 * q4], S[4 * q4 + 1], S[4 * q4 + 2], S[4 * q4 + 3]);
             }
         }
-        __syncthreads();
+        SSM_TRACE(3);
+        lds_barrier();
+        SSM_TRACE(4);
+        tb = t_cur;
+        t_cur = t_nxt;
+        t_nxt = t_nn;
     }
 }
 
@@ -376,7 +433,10 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, hipStrea
     }
     const int n_wg = plan->n_workgroups;
     const int per_xcd = (n_wg + 7) / 8;
-    hipLaunchKernelGGL(ssm_scan_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream, args,
-                       per_xcd, n_wg);
+    hipLaunchKernelGGL(ssm_scan_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
+                       static_cast<const bf16_t *>(args.x), static_cast<const bf16_t *>(args.dt), args.A,
+                       static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C), args.D,
+                       static_cast<bf16_t *>(args.y), args.state_out, args.init_ptrs, args.tiles, args.seqs,
+                       args.H, args.P, args.G, args.p_split, per_xcd, n_wg);
     return hipGetLastError();
 }
