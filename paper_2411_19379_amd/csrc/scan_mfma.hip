@@ -19,21 +19,25 @@
 // The 8 waves of a workgroup are specialised and form a software pipeline
 // over tiles with ONE workgroup barrier per tile:
 //
-//   waves 4,5,7  loaders: global -> LDS for tile k+2 (dt prefix sums and the
-//                per-token factor tables, x raw and decay-weighted, B)
-//   wave  6      off-diagonal score block (tokens 32..63 against 0..31) of
-//                tile k+1, handed over through a per-lane LDS mailbox
-//   waves 0,1    tile k, token half 0 / 1: diagonal score block, masking,
-//                S.C, Gm.x, store of y.  C fragments come straight from
-//                global memory in MFMA layout; the masked scores go from the
-//                accumulators into the next MFMA's operand without LDS.
+//   waves 4,5    loaders: global -> LDS for tile k+2 (B; dt prefix sums, the
+//                per-token factor tables, x raw and decay-weighted), from
+//                registers filled three tiles earlier
+//   waves 6,7    masked score blocks of tile k+1 for the query tokens of half
+//                0 / 1, handed to the output waves through per-lane LDS
+//                mailboxes that already hold the next MFMA's operand
+//   waves 0,1    tile k, token half 0 / 1: S.C, Gm.x, store of y
 //   waves 2,3    tile k: state update for 64 state indices each, bf16 copy of
-//                the new state for tile k+1, checkpoint stores.
+//                the new state for tile k+1, checkpoint stores
+//
+// C fragments come straight from global memory in MFMA layout (prefetched
+// three tiles ahead into a register ring).
 //
 // Products are computed transposed (Gm^T, Y^T, S^T) so every lane holds 4
 // consecutive elements along the destination's fastest axis; token-major
 // tiles are fed to contractions over tokens through the LDS transpose reads
 // of gfx950.
+#include <type_traits>
+
 #include "device_utils.h"
 
 // Optional cycle-trace hooks for profiling builds; they expand to nothing here.
@@ -50,7 +54,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 512;             // 8 waves
 constexpr int kQ = kMfmaTileTokens;  // 64 tokens per tile
 constexpr int kN = 128;              // d_state
 constexpr int kPW = 32;              // channels per workgroup
@@ -72,7 +76,9 @@ struct Lds {
     bf16_t Xr[3][kQ][LDX];   // x as loaded, token major
     bf16_t Xs[3][kQ][LDX];   // e^{l_q-l_j} dt_j x_j, token major
     bf16_t Ss[2][kPW][LDB];  // bf16 copy of the running state, channel major
-    uint4 Gm10[2][64][2];    // off-diagonal score block as the consumer lane's two MFMA operands
+    uint4 M00[2][64][2];     // masked score blocks as the output lane's two MFMA operands:
+    uint4 M11[2][64][2];     //   diagonal block of token half 0 / 1,
+    uint4 M10[2][64][2];     //   off-diagonal block (queries 32..63, keys 0..31)
     Tables tab[3];
 };
 
@@ -171,244 +177,309 @@ __device__ __forceinline__ SsmTile tile_at(const Ctx &c, int k)
     return c.tiles[__builtin_amdgcn_readfirstlane(c.tile_begin + kk)];
 }
 
+// The pipeline loop shared by all roles: steps s = -2 .. n_tiles-1, one
+// workgroup barrier after each.  Steps come in groups of three so that
+// everything indexed by a tile number modulo 3 (LDS buffers, register rings
+// of prefetched data) is addressed statically: in step s = 3m - 2 + u,
+// (s + 2) % 3 == u.
+template <typename F>
+__device__ __forceinline__ void pipe_loop(int n_tiles, F &&body)
+{
+    SSM_TRACE_DECL
+    for (int s0 = -2; s0 < n_tiles; s0 += 3) {
+        if (s0 + 0 < n_tiles) {
+            body(s0 + 0, std::integral_constant<int, 0>{});
+            SSM_TRACE(1);
+            lds_barrier();
+            SSM_TRACE(2);
+        }
+        if (s0 + 1 < n_tiles) {
+            body(s0 + 1, std::integral_constant<int, 1>{});
+            SSM_TRACE(1);
+            lds_barrier();
+            SSM_TRACE(2);
+        }
+        if (s0 + 2 < n_tiles) {
+            body(s0 + 2, std::integral_constant<int, 2>{});
+            SSM_TRACE(1);
+            lds_barrier();
+            SSM_TRACE(2);
+        }
+    }
+}
+
 // C rows [row0, row0+32) of a tile as the B operand of eight 32x32x16 MFMAs:
 // lane -> token row0 + lane%32, state indices 16ks + 8(lane/32) + 0..7.
 __device__ __forceinline__ void load_c_frags(const Ctx &c, const SsmTile &t, int row0, int lane, uint4 (&f)[8])
 {
     const int row = row0 + (lane & 31);
     const bf16_t *p = c.Cg + (((size_t)t.tok0 + row) * c.G + c.g) * kN + 8 * (lane >> 5);
+    if (t.len == kQ) {  // full tile: no predication
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        f[ks] = make_uint4(0, 0, 0, 0);
-        if (row < t.len)
+        for (int ks = 0; ks < 8; ++ks)
             f[ks] = *reinterpret_cast<const uint4 *>(p + 16 * ks);
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            f[ks] = make_uint4(0, 0, 0, 0);
+            if (row < t.len)
+                f[ks] = *reinterpret_cast<const uint4 *>(p + 16 * ks);
+        }
     }
+}
+
+// Mask and decay a diagonal 32x32 score block held as Gm^T accumulators
+// (element r of lane (i = lane%32, q = lane/32) is row j = 8(r/4) + 4q + r%4),
+// add D on the diagonal, and pack it as the two bf16 operands of the Gm.x MFMAs.
+__device__ __forceinline__ void mask_diag(const f32x16 &acc, const Tables &tb, int off, int i, int q, float Dh,
+                                          uint4 &g0, uint4 &g1)
+{
+    const float ell2_i = tb.ell2[off + i];
+    float v[16];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cj[off + 8 * a + 4 * q]);
+        const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int jl = 8 * a + 4 * q + r;
+            float g = jl <= i ? acc[4 * a + r] * exp2_fast(ell2_i - cc[r]) : 0.f;
+            if (jl == i)
+                g += Dh;
+            v[4 * a + r] = g;
+        }
+    }
+    g0 = make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    g1 = make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
 }
 
 // ---------------------------------------------------------------- loaders
-// dt prefix sums, factor tables and the two x tiles of tile k+2.
-__device__ void role_load_x(const Ctx &c, Lds &L, int lane)
+// B rows [32 HALF, 32 HALF + 32) of a tile and, for the wave with WITH_X, the
+// dt prefix sums, the per-token factor tables and the two x tiles.  Written to
+// LDS two tiles ahead of their consumers, from registers filled by global
+// loads three tiles before that.
+template <int HALF, bool WITH_X>
+__device__ __forceinline__ void role_load(const Ctx &c, Lds &L, int lane)
 {
-    uint32_t dt_raw = 0;
-    uint4 xr[4];
-    auto issue = [&](int k) {
-        const SsmTile t = tile_at(c, k);
-        dt_raw = 0;
-        if (lane < t.len)
-            dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int tok = (lane >> 2) + 16 * kk;
-            xr[kk] = make_uint4(0, 0, 0, 0);
-            if (tok < t.len)
-                xr[kk] = *reinterpret_cast<const uint4 *>(c.x + (((size_t)t.tok0 + tok) * c.H + c.h) * c.P +
-                                                          c.pbase + 8 * (lane & 3));
-        }
-    };
-    issue(0);
-    SSM_TRACE_DECL
-    for (int s = -2; s < c.n_tiles; ++s) {
-        const int k = s + 2;
-        if (k < c.n_tiles) {
-            const int b = k % 3;
-            Tables &tb = L.tab[b];
-            const float dtj = __uint_as_float(dt_raw << 16);
-            const float ell2 = wave_inclusive_sum(dtj * c.Ah) * kLog2e;
-            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
-            const float wj = exp2_fast(last - ell2) * dtj;  // weight of token `lane` in the state update
-            tb.ell2[lane] = ell2;
-            tb.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
-            tb.ei[lane] = exp2_fast(ell2);
-            if (lane >= 32)
-                tb.ri[lane - 32] = exp2_fast(ell2 - e31);
-            else
-                tb.cf[lane] = exp2_fast(e31 - ell2) * dtj;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int tok = (lane >> 2) + 16 * kk;
-                const float wt = __shfl(wj, tok, 64);
-                *reinterpret_cast<uint4 *>(&L.Xr[b][tok][8 * (lane & 3)]) = xr[kk];
-                const uint32_t xv[4] = {xr[kk].x, xr[kk].y, xr[kk].z, xr[kk].w};
-                uint32_t o[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    o[e] = pack2(wt * __uint_as_float(xv[e] << 16), wt * __uint_as_float(xv[e] & 0xffff0000u));
-                *reinterpret_cast<uint4 *>(&L.Xs[b][tok][8 * (lane & 3)]) = make_uint4(o[0], o[1], o[2], o[3]);
-            }
-            if (k + 1 < c.n_tiles)
-                issue(k + 1);
-        }
-        SSM_TRACE(1);
-        lds_barrier();
-        SSM_TRACE(2);
-    }
-}
-
-// B rows [32 half, 32 half + 32) of tile k+2.
-__device__ void role_load_b(const Ctx &c, Lds &L, int lane, int half)
-{
-    uint4 r[8];
-    const int row_l = 32 * half + (lane >> 4);
-    auto issue = [&](int k) {
-        const SsmTile t = tile_at(c, k);
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int row = row_l + 4 * kk;
-            r[kk] = make_uint4(0, 0, 0, 0);
-            if (row < t.len)
-                r[kk] = *reinterpret_cast<const uint4 *>(c.Bg + (((size_t)t.tok0 + row) * c.G + c.g) * kN +
-                                                         8 * (lane & 15));
-        }
-    };
-    issue(0);
-    SSM_TRACE_DECL
-    for (int s = -2; s < c.n_tiles; ++s) {
-        const int k = s + 2;
-        if (k < c.n_tiles) {
-            const int b = k % 3;
+    uint4 r[3][8];
+    uint32_t dtr[3] = {0, 0, 0};
+    uint4 xr[3][4];
+    const int row_l = 32 * HALF + (lane >> 4);
+    auto issue = [&](const SsmTile &t, uint4 (&dst)[8], uint32_t &dt_raw, uint4 (&xv)[4]) {
+        const bf16_t *p = c.Bg + (((size_t)t.tok0 + row_l) * c.G + c.g) * kN + 8 * (lane & 15);
+        const size_t step = (size_t)4 * c.G * kN;
+        const bf16_t *px = c.x + (((size_t)t.tok0 + (lane >> 2)) * c.H + c.h) * c.P + c.pbase + 8 * (lane & 3);
+        const size_t xstep = (size_t)16 * c.H * c.P;
+        if (t.len == kQ) {  // full tile: no predication
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                *reinterpret_cast<uint4 *>(&L.Bs[b][row_l + 4 * kk][8 * (lane & 15)]) = r[kk];
-            SSM_TRACE(3);
-            if (k + 1 < c.n_tiles)
-                issue(k + 1);
+                dst[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
+            if (WITH_X) {
+                dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    xv[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                dst[kk] = make_uint4(0, 0, 0, 0);
+                if (row_l + 4 * kk < t.len)
+                    dst[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
+            }
+            if (WITH_X) {
+                dt_raw = 0;
+                if (lane < t.len)
+                    dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    xv[kk] = make_uint4(0, 0, 0, 0);
+                    if ((lane >> 2) + 16 * kk < t.len)
+                        xv[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
+                }
+            }
         }
-        SSM_TRACE(1);
-        lds_barrier();
-        SSM_TRACE(2);
-    }
+    };
+    issue(tile_at(c, 0), r[0], dtr[0], xr[0]);
+    if (1 < c.n_tiles)
+        issue(tile_at(c, 1), r[1], dtr[1], xr[1]);
+    if (2 < c.n_tiles)
+        issue(tile_at(c, 2), r[2], dtr[2], xr[2]);
+    SsmTile dpf = tile_at(c, 3);
+    pipe_loop(c.n_tiles, [&](int s, auto U) {
+        constexpr int u = decltype(U)::value;  // == (s + 2) % 3: ring slot and LDS buffer of tile k
+        const int k = s + 2;
+        if (k < c.n_tiles) {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                *reinterpret_cast<uint4 *>(&L.Bs[u][row_l + 4 * kk][8 * (lane & 15)]) = r[u][kk];
+            if (WITH_X) {
+                Tables &tb = L.tab[u];
+                const float dtj = __uint_as_float(dtr[u] << 16);
+                const float ell2 = wave_inclusive_sum(dtj * c.Ah) * kLog2e;
+                const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
+                const float wj = exp2_fast(last - ell2) * dtj;  // weight of token `lane` in the state update
+                tb.ell2[lane] = ell2;
+                tb.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
+                tb.ei[lane] = exp2_fast(ell2);
+                if (lane >= 32)
+                    tb.ri[lane - 32] = exp2_fast(ell2 - e31);
+                else
+                    tb.cf[lane] = exp2_fast(e31 - ell2) * dtj;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int tok = (lane >> 2) + 16 * kk;
+                    const float wt = __shfl(wj, tok, 64);
+                    const uint4 xq = xr[u][kk];
+                    *reinterpret_cast<uint4 *>(&L.Xr[u][tok][8 * (lane & 3)]) = xq;
+                    const uint32_t xv[4] = {xq.x, xq.y, xq.z, xq.w};
+                    uint32_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = pack2(wt * __uint_as_float(xv[e] << 16), wt * __uint_as_float(xv[e] & 0xffff0000u));
+                    *reinterpret_cast<uint4 *>(&L.Xs[u][tok][8 * (lane & 3)]) = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            }
+            if (k + 3 < c.n_tiles)
+                issue(dpf, r[u], dtr[u], xr[u]);
+            dpf = tile_at(c, k + 4);
+        }
+    });
 }
 
-// ---------------------------------------------------------------- off-diagonal scores of tile k+1
-// Gm^T[j, i] for j in 0..31, i in 32..63: every entry is unmasked and the
-// decay factorises as e^{l_i-l_31} * e^{l_31-l_j} dt_j, both factors <= 1.
-// Accumulator element r of lane (i = lane%32, q = lane/32) is row
-// j = 8(r/4) + 4q + r%4; the consumer's MFMA takes exactly these values as its
-// operand when its other operand lists tokens in the same order, so the packed
-// accumulators are mailed lane to lane.
-__device__ void role_offdiag(const Ctx &c, Lds &L, int lane)
+// ---------------------------------------------------------------- scores of tile k+1, token half IH
+// Gm^T blocks with the query tokens i in half IH.  The diagonal block (keys j
+// in the same half) is masked with one exponential per entry.  For IH = 1 the
+// off-diagonal block (keys 0..31) is unmasked and its decay factorises as
+// e^{l_i-l_31} * e^{l_31-l_j} dt_j, both factors <= 1.  Accumulator element r
+// of lane (i = lane%32, q = lane/32) is key j = 8(r/4) + 4q + r%4; the output
+// wave's MFMA takes exactly these values as its operand when its other operand
+// lists tokens in the same order, so the packed blocks are mailed lane to lane.
+template <int IH>
+__device__ __forceinline__ void role_scores(const Ctx &c, Lds &L, int lane)
 {
-    uint4 cf[8], cn[8];
-    load_c_frags(c, tile_at(c, 0), 32, lane, cf);
-    SSM_TRACE_DECL
-    for (int s = -2; s < c.n_tiles; ++s) {
+    uint4 cfr[3][8];
+    load_c_frags(c, tile_at(c, 0), 32 * IH, lane, cfr[0]);
+    if (1 < c.n_tiles)
+        load_c_frags(c, tile_at(c, 1), 32 * IH, lane, cfr[1]);
+    if (2 < c.n_tiles)
+        load_c_frags(c, tile_at(c, 2), 32 * IH, lane, cfr[2]);
+    SsmTile dpf = tile_at(c, 3);
+    const int i = lane & 31, q = lane >> 5;
+    pipe_loop(c.n_tiles, [&](int s, auto U) {
+        constexpr int u = decltype(U)::value;
+        constexpr int b = (u + 2) % 3;  // == (s + 1) % 3: ring slot and LDS buffer of tile k
         const int k = s + 1;
         if (k >= 0 && k < c.n_tiles) {
-            if (k + 1 < c.n_tiles)
-                load_c_frags(c, tile_at(c, k + 1), 32, lane, cn);
-            const int b = k % 3;
-            f32x16 acc = zero16();
-            const bf16_t *pa = &L.Bs[b][lane & 31][8 * (lane >> 5)];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(pa + 16 * ks),
-                                                              __builtin_bit_cast(bf16x8, cf[ks]), acc, 0, 0, 0);
             const Tables &tb = L.tab[b];
-            const float ri = tb.ri[lane & 31];
-            float v[16];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cf[8 * a + 4 * (lane >> 5)]);
-                v[4 * a + 0] = acc[4 * a + 0] * (ri * c4.x);
-                v[4 * a + 1] = acc[4 * a + 1] * (ri * c4.y);
-                v[4 * a + 2] = acc[4 * a + 2] * (ri * c4.z);
-                v[4 * a + 3] = acc[4 * a + 3] * (ri * c4.w);
-            }
-            L.Gm10[k & 1][lane][0] =
-                __builtin_bit_cast(uint4, pack8(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]));
-            L.Gm10[k & 1][lane][1] =
-                __builtin_bit_cast(uint4, pack8(v[8], v[9], v[10], v[11], v[12], v[13], v[14], v[15]));
+            f32x16 acc = zero16();
+            const bf16_t *pa = &L.Bs[b][32 * IH + i][8 * q];
+            // all LDS fragment reads are issued before the first MFMA needs one
+            bf16x8 fa[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-                cf[ks] = cn[ks];
+                fa[ks] = lds_frag(pa + 16 * ks);
+            if (IH == 0) {
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], __builtin_bit_cast(bf16x8, cfr[b][ks]), acc,
+                                                                  0, 0, 0);
+            } else {
+                f32x16 off = zero16();
+                const bf16_t *po = &L.Bs[b][i][8 * q];
+                bf16x8 fo[8];
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    fo[ks] = lds_frag(po + 16 * ks);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 fc = __builtin_bit_cast(bf16x8, cfr[b][ks]);
+                    off = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[ks], fc, off, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fc, acc, 0, 0, 0);
+                }
+                const float ri = tb.ri[i];
+                float v[16];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cf[8 * a + 4 * q]);
+                    v[4 * a + 0] = off[4 * a + 0] * (ri * c4.x);
+                    v[4 * a + 1] = off[4 * a + 1] * (ri * c4.y);
+                    v[4 * a + 2] = off[4 * a + 2] * (ri * c4.z);
+                    v[4 * a + 3] = off[4 * a + 3] * (ri * c4.w);
+                }
+                L.M10[k & 1][lane][0] =
+                    make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+                L.M10[k & 1][lane][1] =
+                    make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
+            }
+            // this tile's C fragments are spent: reuse the ring slot for tile k+3
+            if (k + 3 < c.n_tiles)
+                load_c_frags(c, dpf, 32 * IH, lane, cfr[b]);
+            dpf = tile_at(c, k + 4);
+            uint4 g0, g1;
+            mask_diag(acc, tb, 32 * IH, i, q, c.Dh, g0, g1);
+            uint4(*M)[64][2] = IH == 0 ? L.M00 : L.M11;
+            M[k & 1][lane][0] = g0;
+            M[k & 1][lane][1] = g1;
         }
-        SSM_TRACE(1);
-        lds_barrier();
-        SSM_TRACE(2);
-    }
+    });
 }
 
 // ---------------------------------------------------------------- outputs of tile k, token half IH
 template <int IH>
-__device__ void role_output(const Ctx &c, Lds &L, int lane)
+__device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
 {
-    uint4 cf[8], cn[8];
-    load_c_frags(c, tile_at(c, 0), 32 * IH, lane, cf);
+    uint4 cfr[3][8];
+    load_c_frags(c, tile_at(c, 0), 32 * IH, lane, cfr[0]);
+    if (1 < c.n_tiles)
+        load_c_frags(c, tile_at(c, 1), 32 * IH, lane, cfr[1]);
+    if (2 < c.n_tiles)
+        load_c_frags(c, tile_at(c, 2), 32 * IH, lane, cfr[2]);
+    SsmTile dpf = tile_at(c, 3);
     const int i = lane & 31, q = lane >> 5;
     // transpose-read addressing: lane group g4 = lane/16 covers channel block
     // g4&1; tokens come in the order 8(e/4) + 4q + e%4, as in the scores
     const int g4 = lane >> 4;
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
     const int tr_row = 4 * (g4 >> 1) + ((lane & 15) >> 2);
-    SsmTile t = tile_at(c, 0);
-    SSM_TRACE_DECL
-    for (int s = -2; s < c.n_tiles; ++s) {
+    pipe_loop(c.n_tiles, [&](int s, auto U) {
+        constexpr int u = decltype(U)::value;
+        constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
         if (s >= 0) {
-            const SsmTile t_next = tile_at(c, s + 1);
-            if (s + 1 < c.n_tiles)
-                load_c_frags(c, t_next, 32 * IH, lane, cn);
-            const int b = s % 3;
-            const Tables &tb = L.tab[b];
-            SSM_TRACE(3);
-
-            // diagonal score block: Gm^T[j, i], j and i in this half
-            f32x16 acc = zero16();
-            const bf16_t *pa = &L.Bs[b][32 * IH + i][8 * q];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(pa + 16 * ks),
-                                                              __builtin_bit_cast(bf16x8, cf[ks]), acc, 0, 0, 0);
+            const SsmTile t = tile_at(c, s);
             // S_s C_i with the state as it was before this tile
             f32x16 Y = zero16();
             const bf16_t *ps = &L.Ss[(s + 1) & 1][i][8 * q];
+            // all LDS reads of the step are issued up front
+            bf16x8 fs[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(ps + 16 * ks),
-                                                            __builtin_bit_cast(bf16x8, cf[ks]), Y, 0, 0, 0);
-            SSM_TRACE(4);
-            // the C fragments of this tile are spent: take over the next tile's
-            // (here, and not after the stores below, so that the wait for these
-            // loads does not also wait for the stores)
+                fs[ks] = lds_frag(ps + 16 * ks);
+            uint4(*M)[64][2] = IH == 0 ? L.M00 : L.M11;
+            const uint4 g0 = M[s & 1][lane][0], g1 = M[s & 1][lane][1];
+            const bf16_t *px = &L.Xr[b][32 * IH + tr_row][tr_col];
+            const bf16x8 x0 = lds_frag_tr(px, px + 8 * LDX), x1 = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
+            const float ei = L.tab[b].ei[32 * IH + i];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-                cf[ks] = cn[ks];
-            SSM_TRACE(5);
-            // mask and decay; D rides on the diagonal
-            const float ell2_i = tb.ell2[32 * IH + i];
-            float v[16];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cj[32 * IH + 8 * a + 4 * q]);
-                const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int jl = 8 * a + 4 * q + r;
-                    float g = jl <= i ? acc[4 * a + r] * exp2_fast(ell2_i - cc[r]) : 0.f;
-                    if (jl == i)
-                        g += c.Dh;
-                    v[4 * a + r] = g;
-                }
-            }
-            const bf16x8 g0 = pack8(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]);
-            const bf16x8 g1 = pack8(v[8], v[9], v[10], v[11], v[12], v[13], v[14], v[15]);
-            const float ei = tb.ei[32 * IH + i];
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], __builtin_bit_cast(bf16x8, cfr[b][ks]), Y, 0, 0, 0);
+            if (s + 3 < c.n_tiles)
+                load_c_frags(c, dpf, 32 * IH, lane, cfr[b]);
+            dpf = tile_at(c, s + 4);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 Y[r] *= ei;
-            SSM_TRACE(6);
-            // intra-tile term: x^T through transpose reads, scores from registers / the mailbox
-            const bf16_t *px = &L.Xr[b][32 * IH + tr_row][tr_col];
-            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px, px + 8 * LDX), g0, Y, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px + 16 * LDX, px + 24 * LDX), g1, Y, 0, 0, 0);
+            // intra-tile term: x^T through transpose reads, masked scores from the mailboxes
+            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, __builtin_bit_cast(bf16x8, g0), Y, 0, 0, 0);
+            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, __builtin_bit_cast(bf16x8, g1), Y, 0, 0, 0);
             if (IH == 1) {
                 const bf16_t *px0 = &L.Xr[b][tr_row][tr_col];
-                const uint4 m0 = L.Gm10[s & 1][lane][0], m1 = L.Gm10[s & 1][lane][1];
+                const uint4 m0 = L.M10[s & 1][lane][0], m1 = L.M10[s & 1][lane][1];
                 Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px0, px0 + 8 * LDX),
                                                             __builtin_bit_cast(bf16x8, m0), Y, 0, 0, 0);
                 Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px0 + 16 * LDX, px0 + 24 * LDX),
                                                             __builtin_bit_cast(bf16x8, m1), Y, 0, 0, 0);
             }
-            SSM_TRACE(7);
             // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of token i
             if (32 * IH + i < t.len) {
                 bf16_t *py = c.y + (((size_t)t.tok0 + 32 * IH + i) * c.H + c.h) * c.P + c.pbase + 4 * q;
@@ -417,16 +488,12 @@ __device__ void role_output(const Ctx &c, Lds &L, int lane)
                     *reinterpret_cast<uint2 *>(py + 8 * a) =
                         make_uint2(pack2(Y[4 * a], Y[4 * a + 1]), pack2(Y[4 * a + 2], Y[4 * a + 3]));
             }
-            t = t_next;
         }
-        SSM_TRACE(1);
-        lds_barrier();
-        SSM_TRACE(2);
-    }
+    });
 }
 
 // ---------------------------------------------------------------- state update of tile k, 64 state indices
-__device__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
+__device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
 {
     // S^T tiles: rows n = 64sw + 32t + 8(r/4) + 4(lane/32) + r%4, column p = lane%32
     const int p = lane & 31, q = lane >> 5;
@@ -450,12 +517,11 @@ __device__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
     const int g4 = lane >> 4;
     const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-    SsmTile t = tile_at(c, 0);
-    SSM_TRACE_DECL
-    for (int s = -2; s < c.n_tiles; ++s) {
+    pipe_loop(c.n_tiles, [&](int s, auto U) {
+        constexpr int u = decltype(U)::value;
+        constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
         if (s >= 0) {
-            const SsmTile t_next = tile_at(c, s + 1);
-            const int b = s % 3;
+            const SsmTile t = tile_at(c, s);
             const float dl = L.tab[b].ei[kQ - 1];  // padded tokens have dt = 0, so this is e^{l_len}
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -464,13 +530,17 @@ __device__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
             }
             const bf16_t *pb = &L.Bs[b][tr_row][64 * sw + tr_col];
             const bf16_t *px = &L.Xs[b][tr_row][tr_col];
+            bf16x8 fx[4], f0[4], f1[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 fx = lds_frag_tr(px + 16 * ks * LDX, px + (16 * ks + 4) * LDX);
-                const bf16x8 f0 = lds_frag_tr(pb + 16 * ks * LDB, pb + (16 * ks + 4) * LDB);
-                const bf16x8 f1 = lds_frag_tr(pb + 16 * ks * LDB + 32, pb + (16 * ks + 4) * LDB + 32);
-                S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, fx, S[0], 0, 0, 0);
-                S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, fx, S[1], 0, 0, 0);
+                fx[ks] = lds_frag_tr(px + 16 * ks * LDX, px + (16 * ks + 4) * LDX);
+                f0[ks] = lds_frag_tr(pb + 16 * ks * LDB, pb + (16 * ks + 4) * LDB);
+                f1[ks] = lds_frag_tr(pb + 16 * ks * LDB + 32, pb + (16 * ks + 4) * LDB + 32);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[ks], fx[ks], S[0], 0, 0, 0);
+                S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks], fx[ks], S[1], 0, 0, 0);
             }
             // bf16 copy for the next tile's S.C product; checkpoint
 #pragma unroll
@@ -485,12 +555,8 @@ __device__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
                                                     (((size_t)t.ckpt_slot * c.H + c.h) * c.P + c.pbase + p) * kN + n0) =
                             make_float4(S[t2][4 * a], S[t2][4 * a + 1], S[t2][4 * a + 2], S[t2][4 * a + 3]);
                 }
-            t = t_next;
         }
-        SSM_TRACE(1);
-        lds_barrier();
-        SSM_TRACE(2);
-    }
+    });
 }
 
 // Pointers are separate __restrict__ parameters (not a struct) so that the
@@ -544,10 +610,10 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     case 1: role_output<1>(c, L, lane); break;
     case 2: role_state(c, L, lane, 0); break;
     case 3: role_state(c, L, lane, 1); break;
-    case 4: role_load_x(c, L, lane); break;
-    case 5: role_load_b(c, L, lane, 0); break;
-    case 6: role_offdiag(c, L, lane); break;
-    default: role_load_b(c, L, lane, 1); break;
+    case 4: role_load<0, false>(c, L, lane); break;
+    case 5: role_load<1, true>(c, L, lane); break;
+    case 6: role_scores<0>(c, L, lane); break;
+    default: role_scores<1>(c, L, lane); break;
     }
 }
 
