@@ -17,25 +17,25 @@
 // exponents, accumulators and checkpoints are fp32.
 //
 // The 8 waves of a workgroup are specialised and form a software pipeline
-// over tiles with ONE workgroup barrier per tile:
+// over tiles with ONE workgroup barrier per tile.  In pipeline step k:
 //
-//   waves 4,5    loaders: global -> LDS for tile k+2 (B; dt prefix sums, the
-//                per-token factor tables, x raw and decay-weighted), from
-//                registers filled three tiles earlier
-//   waves 6,7    masked score blocks of tile k+1 for the query tokens of half
-//                0 / 1, handed to the output waves through per-lane LDS
-//                mailboxes that already hold the next MFMA's operand
-//   waves 0,1    tile k, token half 0 / 1: S.C, Gm.x, store of y
+//   waves 4,5,7  loaders: write tile k+2 into LDS (B; C; dt prefix sums, the
+//                per-token factor tables, x raw and decay-weighted) from
+//                registers filled by coalesced global loads one step earlier
+//   wave  6      off-diagonal score block (queries 32..63, keys 0..31) of
+//                tile k+1, handed over through a per-lane LDS mailbox that
+//                already holds the consumer's MFMA operand
+//   waves 0,1    token half 0 / 1.  For tile k: S.C with the C fragments and
+//                Gm.x with the masked diagonal score block this wave kept in
+//                registers from the step before, y staged through LDS and
+//                stored with coalesced writes.  For tile k+1: C fragments from
+//                LDS, diagonal score block, masking.
 //   waves 2,3    tile k: state update for 64 state indices each, bf16 copy of
 //                the new state for tile k+1, checkpoint stores
 //
-// C fragments come straight from global memory in MFMA layout (prefetched
-// three tiles ahead into a register ring).
-//
-// Products are computed transposed (Gm^T, Y^T, S^T) so every lane holds 4
-// consecutive elements along the destination's fastest axis; token-major
-// tiles are fed to contractions over tokens through the LDS transpose reads
-// of gfx950.
+// Every global access is laid out so that four neighbouring lanes touch one
+// 64-byte segment; MFMA operand layouts are produced from LDS, never from
+// global memory directly.
 #include <type_traits>
 
 #include "device_utils.h"
@@ -60,6 +60,7 @@ constexpr int kN = 128;              // d_state
 constexpr int kPW = 32;              // channels per workgroup
 constexpr int LDB = kN + 16;         // row stride (elements) of the B and state tiles
 constexpr int LDX = kPW;             // row stride of the x tiles (unpadded on purpose)
+constexpr int LDY = kPW + 8;         // row stride of the y staging tiles
 constexpr float kLog2e = 1.4426950408889634f;
 
 // per-token factors of one tile
@@ -72,13 +73,13 @@ struct Tables {
 };
 
 struct Lds {
-    bf16_t Bs[3][kQ][LDB];   // B tile, token major
-    bf16_t Xr[3][kQ][LDX];   // x as loaded, token major
-    bf16_t Xs[3][kQ][LDX];   // e^{l_q-l_j} dt_j x_j, token major
-    bf16_t Ss[2][kPW][LDB];  // bf16 copy of the running state, channel major
-    uint4 M00[2][64][2];     // masked score blocks as the output lane's two MFMA operands:
-    uint4 M11[2][64][2];     //   diagonal block of token half 0 / 1,
-    uint4 M10[2][64][2];     //   off-diagonal block (queries 32..63, keys 0..31)
+    bf16_t Bs[3][kQ][LDB];        // B tile, token major
+    bf16_t Cs[2][kQ][LDB];        // C tile, token major
+    bf16_t Xr[3][kQ][LDX];        // x as loaded, token major
+    bf16_t Xs[3][kQ][LDX];        // e^{l_q-l_j} dt_j x_j, token major
+    bf16_t Ss[2][kPW][LDB];       // bf16 copy of the running state, channel major
+    uint4 M10[2][64][2];          // off-diagonal score block as the consumer lane's two MFMA operands
+    bf16_t Ys[2][kQ / 2][LDY];    // y of one token half on its way to coalesced stores
     Tables tab[3];
 };
 
@@ -185,25 +186,18 @@ __device__ __forceinline__ SsmTile tile_at(const Ctx &c, int k)
 template <typename F>
 __device__ __forceinline__ void pipe_loop(int n_tiles, F &&body)
 {
-    SSM_TRACE_DECL
     for (int s0 = -2; s0 < n_tiles; s0 += 3) {
         if (s0 + 0 < n_tiles) {
             body(s0 + 0, std::integral_constant<int, 0>{});
-            SSM_TRACE(1);
             lds_barrier();
-            SSM_TRACE(2);
         }
         if (s0 + 1 < n_tiles) {
             body(s0 + 1, std::integral_constant<int, 1>{});
-            SSM_TRACE(1);
             lds_barrier();
-            SSM_TRACE(2);
         }
         if (s0 + 2 < n_tiles) {
             body(s0 + 2, std::integral_constant<int, 2>{});
-            SSM_TRACE(1);
             lds_barrier();
-            SSM_TRACE(2);
         }
     }
 }
@@ -254,241 +248,274 @@ __device__ __forceinline__ void mask_diag(const f32x16 &acc, const Tables &tb, i
 }
 
 // ---------------------------------------------------------------- loaders
-// B rows [32 HALF, 32 HALF + 32) of a tile and, for the wave with WITH_X, the
-// dt prefix sums, the per-token factor tables and the two x tiles.  Written to
-// LDS two tiles ahead of their consumers, from registers filled by global
-// loads three tiles before that.
-template <int HALF, bool WITH_X>
-__device__ __forceinline__ void role_load(const Ctx &c, Lds &L, int lane)
+// One 64 x 128 bf16 tile (B or C) per step: 16 coalesced 16-byte loads per
+// lane (16 lanes per token row), written to LDS one step after they were
+// issued and two tiles ahead of the consumers.
+template <bool IS_C>
+__device__ __forceinline__ void role_load_bc(const Ctx &c, Lds &L, int lane)
 {
-    uint4 r[3][8];
-    uint32_t dtr[3] = {0, 0, 0};
-    uint4 xr[3][4];
-    const int row_l = 32 * HALF + (lane >> 4);
-    auto issue = [&](const SsmTile &t, uint4 (&dst)[8], uint32_t &dt_raw, uint4 (&xv)[4]) {
-        const bf16_t *p = c.Bg + (((size_t)t.tok0 + row_l) * c.G + c.g) * kN + 8 * (lane & 15);
+    uint4 r[16];
+    const bf16_t *src = IS_C ? c.Cg : c.Bg;
+    const int row_l = lane >> 4, col = 8 * (lane & 15);
+    auto issue = [&](const SsmTile &t) {
+        const bf16_t *p = src + (((size_t)t.tok0 + row_l) * c.G + c.g) * kN + col;
         const size_t step = (size_t)4 * c.G * kN;
-        const bf16_t *px = c.x + (((size_t)t.tok0 + (lane >> 2)) * c.H + c.h) * c.P + c.pbase + 8 * (lane & 3);
-        const size_t xstep = (size_t)16 * c.H * c.P;
         if (t.len == kQ) {  // full tile: no predication
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                dst[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
-            if (WITH_X) {
-                dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    xv[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
-            }
+            for (int kk = 0; kk < 16; ++kk)
+                r[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
         } else {
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                dst[kk] = make_uint4(0, 0, 0, 0);
+            for (int kk = 0; kk < 16; ++kk) {
+                r[kk] = make_uint4(0, 0, 0, 0);
                 if (row_l + 4 * kk < t.len)
-                    dst[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
-            }
-            if (WITH_X) {
-                dt_raw = 0;
-                if (lane < t.len)
-                    dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    xv[kk] = make_uint4(0, 0, 0, 0);
-                    if ((lane >> 2) + 16 * kk < t.len)
-                        xv[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
-                }
+                    r[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
             }
         }
     };
-    issue(tile_at(c, 0), r[0], dtr[0], xr[0]);
-    if (1 < c.n_tiles)
-        issue(tile_at(c, 1), r[1], dtr[1], xr[1]);
-    if (2 < c.n_tiles)
-        issue(tile_at(c, 2), r[2], dtr[2], xr[2]);
-    SsmTile dpf = tile_at(c, 3);
+    issue(tile_at(c, 0));
+    SsmTile dpf = tile_at(c, 1);
+    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;  // == (s + 2) % 3: ring slot and LDS buffer of tile k
+        constexpr int u = decltype(U)::value;  // == (s + 2) % 3: LDS buffer of tile k in a ring of three
         const int k = s + 2;
         if (k < c.n_tiles) {
+            bf16_t(*dst)[LDB] = IS_C ? L.Cs[k & 1] : L.Bs[u];
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                *reinterpret_cast<uint4 *>(&L.Bs[u][row_l + 4 * kk][8 * (lane & 15)]) = r[u][kk];
-            if (WITH_X) {
-                Tables &tb = L.tab[u];
-                const float dtj = __uint_as_float(dtr[u] << 16);
-                const float ell2 = wave_inclusive_sum(dtj * c.Ah) * kLog2e;
-                const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
-                const float wj = exp2_fast(last - ell2) * dtj;  // weight of token `lane` in the state update
-                tb.ell2[lane] = ell2;
-                tb.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
-                tb.ei[lane] = exp2_fast(ell2);
-                if (lane >= 32)
-                    tb.ri[lane - 32] = exp2_fast(ell2 - e31);
-                else
-                    tb.cf[lane] = exp2_fast(e31 - ell2) * dtj;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int tok = (lane >> 2) + 16 * kk;
-                    const float wt = __shfl(wj, tok, 64);
-                    const uint4 xq = xr[u][kk];
-                    *reinterpret_cast<uint4 *>(&L.Xr[u][tok][8 * (lane & 3)]) = xq;
-                    const uint32_t xv[4] = {xq.x, xq.y, xq.z, xq.w};
-                    uint32_t o[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = pack2(wt * __uint_as_float(xv[e] << 16), wt * __uint_as_float(xv[e] & 0xffff0000u));
-                    *reinterpret_cast<uint4 *>(&L.Xs[u][tok][8 * (lane & 3)]) = make_uint4(o[0], o[1], o[2], o[3]);
-                }
-            }
-            if (k + 3 < c.n_tiles)
-                issue(dpf, r[u], dtr[u], xr[u]);
-            dpf = tile_at(c, k + 4);
+            for (int kk = 0; kk < 16; ++kk)
+                *reinterpret_cast<uint4 *>(&dst[row_l + 4 * kk][col]) = r[kk];
+            if (k + 1 < c.n_tiles)
+                issue(dpf);
+            dpf = tile_at(c, k + 2);
         }
+        SSM_TRACE(1);
     });
 }
 
-// ---------------------------------------------------------------- scores of tile k+1, token half IH
-// Gm^T blocks with the query tokens i in half IH.  The diagonal block (keys j
-// in the same half) is masked with one exponential per entry.  For IH = 1 the
-// off-diagonal block (keys 0..31) is unmasked and its decay factorises as
-// e^{l_i-l_31} * e^{l_31-l_j} dt_j, both factors <= 1.  Accumulator element r
-// of lane (i = lane%32, q = lane/32) is key j = 8(r/4) + 4q + r%4; the output
-// wave's MFMA takes exactly these values as its operand when its other operand
-// lists tokens in the same order, so the packed blocks are mailed lane to lane.
-template <int IH>
-__device__ __forceinline__ void role_scores(const Ctx &c, Lds &L, int lane)
+// dt prefix sums, the per-token factor tables and the two x tiles.
+__device__ __forceinline__ void role_load_x(const Ctx &c, Lds &L, int lane)
 {
-    uint4 cfr[3][8];
-    load_c_frags(c, tile_at(c, 0), 32 * IH, lane, cfr[0]);
-    if (1 < c.n_tiles)
-        load_c_frags(c, tile_at(c, 1), 32 * IH, lane, cfr[1]);
-    if (2 < c.n_tiles)
-        load_c_frags(c, tile_at(c, 2), 32 * IH, lane, cfr[2]);
-    SsmTile dpf = tile_at(c, 3);
+    uint32_t dt_raw = 0;
+    uint4 xr[4];
+    auto issue = [&](const SsmTile &t) {
+        const bf16_t *px = c.x + (((size_t)t.tok0 + (lane >> 2)) * c.H + c.h) * c.P + c.pbase + 8 * (lane & 3);
+        const size_t xstep = (size_t)16 * c.H * c.P;
+        dt_raw = 0;
+        if (lane < t.len)
+            dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            xr[kk] = make_uint4(0, 0, 0, 0);
+            if ((lane >> 2) + 16 * kk < t.len)
+                xr[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
+        }
+    };
+    issue(tile_at(c, 0));
+    SsmTile dpf = tile_at(c, 1);
+    SSM_TRACE_DECL
+    pipe_loop(c.n_tiles, [&](int s, auto U) {
+        constexpr int u = decltype(U)::value;  // == (s + 2) % 3
+        const int k = s + 2;
+        if (k < c.n_tiles) {
+            Tables &tb = L.tab[u];
+            const float dtj = __uint_as_float(dt_raw << 16);
+            const float ell2 = wave_inclusive_sum(dtj * c.Ah) * kLog2e;
+            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
+            const float wj = exp2_fast(last - ell2) * dtj;  // weight of token `lane` in the state update
+            tb.ell2[lane] = ell2;
+            tb.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
+            tb.ei[lane] = exp2_fast(ell2);
+            if (lane >= 32)
+                tb.ri[lane - 32] = exp2_fast(ell2 - e31);
+            else
+                tb.cf[lane] = exp2_fast(e31 - ell2) * dtj;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int tok = (lane >> 2) + 16 * kk;
+                const float wt = __shfl(wj, tok, 64);
+                const uint4 xq = xr[kk];
+                *reinterpret_cast<uint4 *>(&L.Xr[u][tok][8 * (lane & 3)]) = xq;
+                const uint32_t xv[4] = {xq.x, xq.y, xq.z, xq.w};
+                uint32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[e] = pack2(wt * __uint_as_float(xv[e] << 16), wt * __uint_as_float(xv[e] & 0xffff0000u));
+                *reinterpret_cast<uint4 *>(&L.Xs[u][tok][8 * (lane & 3)]) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            if (k + 1 < c.n_tiles)
+                issue(dpf);
+            dpf = tile_at(c, k + 2);
+        }
+        SSM_TRACE(1);
+    });
+}
+
+// ---------------------------------------------------------------- off-diagonal scores of tile k+1
+// Gm^T[j, i] for keys j in 0..31 and queries i in 32..63: every entry is
+// unmasked and the decay factorises as e^{l_i-l_31} * e^{l_31-l_j} dt_j, both
+// factors <= 1.  Accumulator element r of lane (i = lane%32, q = lane/32) is key
+// j = 8(r/4) + 4q + r%4; the consumer's MFMA takes exactly these values as its
+// operand when its other operand lists tokens in the same order, so the packed
+// block is mailed lane to lane.
+__device__ __forceinline__ void role_offdiag(const Ctx &c, Lds &L, int lane)
+{
     const int i = lane & 31, q = lane >> 5;
+    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
-        constexpr int b = (u + 2) % 3;  // == (s + 1) % 3: ring slot and LDS buffer of tile k
+        constexpr int b = (u + 2) % 3;  // == (s + 1) % 3
         const int k = s + 1;
         if (k >= 0 && k < c.n_tiles) {
             const Tables &tb = L.tab[b];
+            const bf16_t *pa = &L.Bs[b][i][8 * q];
+            const bf16_t *pc = &L.Cs[k & 1][32 + i][8 * q];
+            bf16x8 fa[8], fc[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                fa[ks] = lds_frag(pa + 16 * ks);
+                fc[ks] = lds_frag(pc + 16 * ks);
+            }
+            const float ri = tb.ri[i];
+            float4 c4[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                c4[a] = *reinterpret_cast<const float4 *>(&tb.cf[8 * a + 4 * q]);
             f32x16 acc = zero16();
-            const bf16_t *pa = &L.Bs[b][32 * IH + i][8 * q];
-            // all LDS fragment reads are issued before the first MFMA needs one
-            bf16x8 fa[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-                fa[ks] = lds_frag(pa + 16 * ks);
-            if (IH == 0) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fc[ks], acc, 0, 0, 0);
+            float v[16];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], __builtin_bit_cast(bf16x8, cfr[b][ks]), acc,
-                                                                  0, 0, 0);
-            } else {
-                f32x16 off = zero16();
-                const bf16_t *po = &L.Bs[b][i][8 * q];
-                bf16x8 fo[8];
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    fo[ks] = lds_frag(po + 16 * ks);
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 fc = __builtin_bit_cast(bf16x8, cfr[b][ks]);
-                    off = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[ks], fc, off, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fc, acc, 0, 0, 0);
-                }
-                const float ri = tb.ri[i];
-                float v[16];
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cf[8 * a + 4 * q]);
-                    v[4 * a + 0] = off[4 * a + 0] * (ri * c4.x);
-                    v[4 * a + 1] = off[4 * a + 1] * (ri * c4.y);
-                    v[4 * a + 2] = off[4 * a + 2] * (ri * c4.z);
-                    v[4 * a + 3] = off[4 * a + 3] * (ri * c4.w);
-                }
-                L.M10[k & 1][lane][0] =
-                    make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-                L.M10[k & 1][lane][1] =
-                    make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
+            for (int a = 0; a < 4; ++a) {
+                v[4 * a + 0] = acc[4 * a + 0] * (ri * c4[a].x);
+                v[4 * a + 1] = acc[4 * a + 1] * (ri * c4[a].y);
+                v[4 * a + 2] = acc[4 * a + 2] * (ri * c4[a].z);
+                v[4 * a + 3] = acc[4 * a + 3] * (ri * c4[a].w);
             }
-            // this tile's C fragments are spent: reuse the ring slot for tile k+3
-            if (k + 3 < c.n_tiles)
-                load_c_frags(c, dpf, 32 * IH, lane, cfr[b]);
-            dpf = tile_at(c, k + 4);
-            uint4 g0, g1;
-            mask_diag(acc, tb, 32 * IH, i, q, c.Dh, g0, g1);
-            uint4(*M)[64][2] = IH == 0 ? L.M00 : L.M11;
-            M[k & 1][lane][0] = g0;
-            M[k & 1][lane][1] = g1;
+            L.M10[k & 1][lane][0] =
+                make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+            L.M10[k & 1][lane][1] =
+                make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
         }
+        SSM_TRACE(1);
     });
 }
 
-// ---------------------------------------------------------------- outputs of tile k, token half IH
+// ---------------------------------------------------------------- token half IH: outputs of tile k, scores of tile k+1
 template <int IH>
-__device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
+__device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
 {
-    uint4 cfr[3][8];
-    load_c_frags(c, tile_at(c, 0), 32 * IH, lane, cfr[0]);
-    if (1 < c.n_tiles)
-        load_c_frags(c, tile_at(c, 1), 32 * IH, lane, cfr[1]);
-    if (2 < c.n_tiles)
-        load_c_frags(c, tile_at(c, 2), 32 * IH, lane, cfr[2]);
-    SsmTile dpf = tile_at(c, 3);
     const int i = lane & 31, q = lane >> 5;
     // transpose-read addressing: lane group g4 = lane/16 covers channel block
     // g4&1; tokens come in the order 8(e/4) + 4q + e%4, as in the scores
     const int g4 = lane >> 4;
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
     const int tr_row = 4 * (g4 >> 1) + ((lane & 15) >> 2);
+    // carried from the scores part of one step to the outputs part of the next
+    bf16x8 cf[8];       // C fragments of this half
+    uint4 g0, g1;       // masked diagonal score block as two MFMA operands
+    g0 = g1 = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        cf[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
-        constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
+        constexpr int b = (u + 1) % 3;   // == s % 3 for s >= 0
+        constexpr int bn = (u + 2) % 3;  // == (s + 1) % 3
+        // ---- LDS reads of both parts, issued before anything waits for them ----
+        bf16x8 fs[8], x0, x1, x2, x3;
+        uint4 m0, m1;
+        float ei = 0.f;
         if (s >= 0) {
-            const SsmTile t = tile_at(c, s);
-            // S_s C_i with the state as it was before this tile
-            f32x16 Y = zero16();
             const bf16_t *ps = &L.Ss[(s + 1) & 1][i][8 * q];
-            // all LDS reads of the step are issued up front
-            bf16x8 fs[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
                 fs[ks] = lds_frag(ps + 16 * ks);
-            uint4(*M)[64][2] = IH == 0 ? L.M00 : L.M11;
-            const uint4 g0 = M[s & 1][lane][0], g1 = M[s & 1][lane][1];
             const bf16_t *px = &L.Xr[b][32 * IH + tr_row][tr_col];
-            const bf16x8 x0 = lds_frag_tr(px, px + 8 * LDX), x1 = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
-            const float ei = L.tab[b].ei[32 * IH + i];
+            x0 = lds_frag_tr(px, px + 8 * LDX);
+            x1 = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
+            if (IH == 1) {
+                const bf16_t *px0 = &L.Xr[b][tr_row][tr_col];
+                x2 = lds_frag_tr(px0, px0 + 8 * LDX);
+                x3 = lds_frag_tr(px0 + 16 * LDX, px0 + 24 * LDX);
+                m0 = L.M10[s & 1][lane][0];
+                m1 = L.M10[s & 1][lane][1];
+            }
+            ei = L.tab[b].ei[32 * IH + i];
+        }
+        bf16x8 cn[8], fb[8];
+        const bool have_next = s + 1 < c.n_tiles;
+        if (have_next) {
+            const bf16_t *pc = &L.Cs[(s + 1) & 1][32 * IH + i][8 * q];
+            const bf16_t *pb = &L.Bs[bn][32 * IH + i][8 * q];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                cn[ks] = lds_frag(pc + 16 * ks);
+                fb[ks] = lds_frag(pb + 16 * ks);
+            }
+        }
+        SSM_TRACE(3);
+        // Two independent MFMA chains back to back: first the diagonal score
+        // block of tile s+1, then S.C of tile s.  The vector-ALU masking of the
+        // first overlaps the matrix work of the second.
+        f32x16 acc = zero16(), Y = zero16();
+        if (have_next) {
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], __builtin_bit_cast(bf16x8, cfr[b][ks]), Y, 0, 0, 0);
-            if (s + 3 < c.n_tiles)
-                load_c_frags(c, dpf, 32 * IH, lane, cfr[b]);
-            dpf = tile_at(c, s + 4);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], cn[ks], acc, 0, 0, 0);
+        }
+        if (s >= 0) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], cf[ks], Y, 0, 0, 0);
+        }
+        SSM_TRACE(4);
+        uint4 gn0 = make_uint4(0, 0, 0, 0), gn1 = gn0;
+        if (have_next)
+            mask_diag(acc, L.tab[bn], 32 * IH, i, q, c.Dh, gn0, gn1);
+        SSM_TRACE(5);
+        // ---- outputs of tile s ----
+        if (s >= 0) {
+            const SsmTile t = tile_at(c, s);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 Y[r] *= ei;
-            // intra-tile term: x^T through transpose reads, masked scores from the mailboxes
             Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, __builtin_bit_cast(bf16x8, g0), Y, 0, 0, 0);
             Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, __builtin_bit_cast(bf16x8, g1), Y, 0, 0, 0);
             if (IH == 1) {
-                const bf16_t *px0 = &L.Xr[b][tr_row][tr_col];
-                const uint4 m0 = L.M10[s & 1][lane][0], m1 = L.M10[s & 1][lane][1];
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px0, px0 + 8 * LDX),
-                                                            __builtin_bit_cast(bf16x8, m0), Y, 0, 0, 0);
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(px0 + 16 * LDX, px0 + 24 * LDX),
-                                                            __builtin_bit_cast(bf16x8, m1), Y, 0, 0, 0);
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2, __builtin_bit_cast(bf16x8, m0), Y, 0, 0, 0);
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x3, __builtin_bit_cast(bf16x8, m1), Y, 0, 0, 0);
             }
-            // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of token i
-            if (32 * IH + i < t.len) {
-                bf16_t *py = c.y + (((size_t)t.tok0 + 32 * IH + i) * c.H + c.h) * c.P + c.pbase + 4 * q;
+            // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of
+            // token i.  Through this wave's own LDS tile to token-major rows, then
+            // 16 bytes per lane with four lanes per 64-byte row of y.
+            SSM_TRACE(6);
+            bf16_t(*ys)[LDY] = L.Ys[IH];
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    *reinterpret_cast<uint2 *>(py + 8 * a) =
-                        make_uint2(pack2(Y[4 * a], Y[4 * a + 1]), pack2(Y[4 * a + 2], Y[4 * a + 3]));
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<uint2 *>(&ys[i][8 * a + 4 * q]) =
+                    make_uint2(pack2(Y[4 * a], Y[4 * a + 1]), pack2(Y[4 * a + 2], Y[4 * a + 3]));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // same wave: LDS executes in order
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const int tok = (lane >> 2) + 16 * m;
+                const uint4 o = *reinterpret_cast<const uint4 *>(&ys[tok][8 * (lane & 3)]);
+                if (32 * IH + tok < t.len)
+                    *reinterpret_cast<uint4 *>(c.y + (((size_t)t.tok0 + 32 * IH + tok) * c.H + c.h) * c.P + c.pbase +
+                                               8 * (lane & 3)) = o;
             }
         }
+        SSM_TRACE(7);
+        // the scores part hands its C fragments and masked block to the next step
+        if (have_next) {
+            g0 = gn0;
+            g1 = gn1;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                cf[ks] = cn[ks];
+        }
+        SSM_TRACE(1);
     });
 }
 
@@ -517,6 +544,7 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int s
     const int g4 = lane >> 4;
     const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
+    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
         constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
@@ -556,6 +584,7 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int s
                             make_float4(S[t2][4 * a], S[t2][4 * a + 1], S[t2][4 * a + 2], S[t2][4 * a + 3]);
                 }
         }
+        SSM_TRACE(1);
     });
 }
 
@@ -606,14 +635,14 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
 
     // Every role runs the same number of barriers: n_tiles + 2 pipeline steps.
     switch (w) {
-    case 0: role_output<0>(c, L, lane); break;
-    case 1: role_output<1>(c, L, lane); break;
+    case 0: role_half<0>(c, L, lane); break;
+    case 1: role_half<1>(c, L, lane); break;
     case 2: role_state(c, L, lane, 0); break;
     case 3: role_state(c, L, lane, 1); break;
-    case 4: role_load<0, false>(c, L, lane); break;
-    case 5: role_load<1, true>(c, L, lane); break;
-    case 6: role_scores<0>(c, L, lane); break;
-    default: role_scores<1>(c, L, lane); break;
+    case 4: role_load_bc<false>(c, L, lane); break;
+    case 5: role_load_bc<true>(c, L, lane); break;
+    case 6: role_offdiag(c, L, lane); break;
+    default: role_load_x(c, L, lane); break;
     }
 }
 
