@@ -1,0 +1,132 @@
+"""Host side of the library without a GPU: the C ABI loads and exports every
+symbol the header declares, argument validation returns the documented error
+codes, and the tile table cuts sequences exactly as the scan needs."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2411_19379_amd as ssm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ssm.load_library()
+    header = open(os.path.join(ROOT, "include", "ssm_prefill.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(ssm_[a-z_]+)\s*\(", header))
+    assert names == {"ssm_plan_create", "ssm_plan_info", "ssm_plan_tile", "ssm_plan_workspace_bytes",
+                     "ssm_prefill", "ssm_plan_destroy", "ssm_last_error"}
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+
+
+def tiles_of(plan):
+    return plan.tiles()  # (tok0, len, seq, ckpt_slot)
+
+
+def check_cover(plan, cu, ckpt_pos, tile_tokens):
+    """Tiles are sequence-local, in order, no longer than the tile size, cover
+    every token once, and a tile ends at every checkpoint with the right slot."""
+    tiles = tiles_of(plan)
+    slot = 0
+    ti = 0
+    for s in range(len(cu) - 1):
+        pos = int(cu[s])
+        ends = {int(cu[s]) + p: None for p in ckpt_pos[s]}
+        for p in ckpt_pos[s]:
+            ends[int(cu[s]) + p] = slot
+            slot += 1
+        while pos < cu[s + 1]:
+            tok0, ln, seq, cs = tiles[ti]
+            assert tok0 == pos and seq == s and 1 <= ln <= tile_tokens
+            inside = [e for e in ends if pos < e < pos + ln]
+            assert not inside, "a checkpoint falls strictly inside a tile"
+            pos += ln
+            assert cs == (ends[pos] if pos in ends else -1)
+            ti += 1
+    assert ti == len(tiles) and slot == plan.info.n_ckpt
+
+
+def test_paper_position_example_tiles():
+    """100 tokens, chunk 32, states wanted at 64 (chunk boundary), 80 and 100:
+    a tile ends exactly at each of them (Section 4.1)."""
+    with open(os.path.join(GOLDEN, "position_example.txt")) as f:
+        total, chunk, want, boundary, rest = (int(v) for v in
+                                              [ln for ln in f if ln.strip() and not ln.startswith("#")][0].split())
+    plan = ssm.Plan(4, 16, 16, 1, chunk, "f32", [0, total], [[boundary, want, total]])
+    check_cover(plan, [0, total], [[boundary, want, total]], plan.info.tile_tokens)
+    ends = [t[0] + t[1] for t in tiles_of(plan) if t[3] >= 0]
+    assert ends == [boundary, want, total]
+    # the second pass of a two-pass prefill is a plan over the remaining tokens
+    plan2 = ssm.Plan(4, 16, 16, 1, chunk, "f32", [0, rest], [[rest]])
+    assert sum(t[1] for t in tiles_of(plan2)) == rest
+
+
+@pytest.mark.parametrize("io,shape,path,tile", [("f32", (4, 16, 16, 1), ssm.SSM_PATH_VALU_F32, 16),
+                                                ("bf16", (128, 64, 128, 8), ssm.SSM_PATH_MFMA_BF16, 64),
+                                                ("bf16", (6, 24, 40, 3), ssm.SSM_PATH_VALU_F32, 16)])
+def test_random_batches_are_covered(io, shape, path, tile):
+    rs = np.random.RandomState(7)
+    H, P, N, G = shape
+    for trial in range(20):
+        nb = int(rs.randint(1, 9))
+        lens = [int(v) for v in rs.randint(0, 400, size=nb)]
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        ck = [sorted(set(int(v) for v in rs.randint(1, L + 1, size=rs.randint(0, 4)))) if L else [] for L in lens]
+        plan = ssm.Plan(H, P, N, G, 256, io, cu, ck)
+        assert plan.info.path == path and plan.info.tile_tokens == tile
+        assert plan.info.total_tokens == cu[-1] and plan.info.batch == nb
+        check_cover(plan, cu, ck, tile)
+        assert ssm.ssm_plan_workspace_bytes(plan.handle) == 0
+        split = P // 32 if path == ssm.SSM_PATH_MFMA_BF16 else 1
+        assert plan.info.n_workgroups == nb * H * split
+        plan.close()
+
+
+def test_chunk_bounds_the_tile():
+    p16 = ssm.Plan(4, 64, 128, 2, 16, "bf16", [0, 100], None)
+    assert p16.info.tile_tokens == 16 and p16.info.n_tiles == 7
+    p256 = ssm.Plan(4, 64, 128, 2, 256, "bf16", [0, 100], None)
+    assert p256.info.tile_tokens == 64 and p256.info.n_tiles == 2
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(cu=[1, 5]), "SSM_ERR_BAD_CU_SEQLENS"),
+    (dict(cu=[0, 5, 3]), "SSM_ERR_BAD_CU_SEQLENS"),
+    (dict(ck=[[0]]), "SSM_ERR_BAD_CHECKPOINT"),
+    (dict(ck=[[11]]), "SSM_ERR_BAD_CHECKPOINT"),
+    (dict(ck=[[4, 4]]), "SSM_ERR_BAD_CHECKPOINT"),
+    (dict(ck=[[7, 3]]), "SSM_ERR_BAD_CHECKPOINT"),
+    (dict(shape=(4, 16, 16, 3)), "SSM_ERR_INVALID_ARG"),
+    (dict(shape=(0, 16, 16, 1)), "SSM_ERR_INVALID_ARG"),
+    (dict(chunk=8), "SSM_ERR_UNSUPPORTED_SHAPE"),
+    (dict(chunk=100), "SSM_ERR_UNSUPPORTED_SHAPE"),
+    (dict(shape=(4, 6, 16, 1)), "SSM_ERR_UNSUPPORTED_SHAPE"),       # 24-byte rows of x
+    (dict(shape=(2, 128, 256, 1)), "SSM_ERR_UNSUPPORTED_SHAPE"),    # fp32 state too large for the VALU kernel
+])
+def test_rejected_arguments(kwargs, status):
+    shape = kwargs.get("shape", (4, 16, 16, 1))
+    cu = kwargs.get("cu", [0, 10])
+    ck = kwargs.get("ck", None)
+    if ck is not None and len(ck) != len(cu) - 1:
+        ck = ck + [[]] * (len(cu) - 1 - len(ck))
+    with pytest.raises(ssm.SsmError) as e:
+        ssm.Plan(*shape, kwargs.get("chunk", 64), "f32", cu, ck)
+    assert e.value.status == status
+    assert ssm.ssm_last_error() != ""
+
+
+def test_null_arguments_and_destroy():
+    lib = ssm.load_library()
+    assert lib.ssm_plan_create(None, 1, None, None, None, None) == -1
+    lib.ssm_plan_destroy(None)  # accepted
+    plan = ssm.Plan(4, 16, 16, 1, 64, "f32", [0, 0, 0], [[], []])
+    assert plan.info.n_tiles == 0 and plan.info.total_tokens == 0
+    with pytest.raises(ssm.SsmError):
+        ssm.ssm_plan_tile(plan.handle, 0)
+    plan.close()
+    plan.close()  # idempotent
