@@ -40,11 +40,6 @@
 
 #include "device_utils.h"
 
-// Optional cycle-trace hooks for profiling builds; they expand to nothing here.
-#ifndef SSM_TRACE
-#define SSM_TRACE(slot)
-#define SSM_TRACE_DECL
-#endif
 
 namespace {
 
@@ -148,13 +143,6 @@ __device__ __forceinline__ f32x16 zero16()
     return z;
 }
 
-__device__ __forceinline__ bf16x8 pack8(float v0, float v1, float v2, float v3, float v4, float v5, float v6,
-                                        float v7)
-{
-    const uint4 u = make_uint4(pack2(v0, v1), pack2(v2, v3), pack2(v4, v5), pack2(v6, v7));
-    return __builtin_bit_cast(bf16x8, u);
-}
-
 // What every role needs to know; all members are wave-uniform.
 struct Ctx {
     const bf16_t *__restrict__ x;
@@ -198,26 +186,6 @@ __device__ __forceinline__ void pipe_loop(int n_tiles, F &&body)
         if (s0 + 2 < n_tiles) {
             body(s0 + 2, std::integral_constant<int, 2>{});
             lds_barrier();
-        }
-    }
-}
-
-// C rows [row0, row0+32) of a tile as the B operand of eight 32x32x16 MFMAs:
-// lane -> token row0 + lane%32, state indices 16ks + 8(lane/32) + 0..7.
-__device__ __forceinline__ void load_c_frags(const Ctx &c, const SsmTile &t, int row0, int lane, uint4 (&f)[8])
-{
-    const int row = row0 + (lane & 31);
-    const bf16_t *p = c.Cg + (((size_t)t.tok0 + row) * c.G + c.g) * kN + 8 * (lane >> 5);
-    if (t.len == kQ) {  // full tile: no predication
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            f[ks] = *reinterpret_cast<const uint4 *>(p + 16 * ks);
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            f[ks] = make_uint4(0, 0, 0, 0);
-            if (row < t.len)
-                f[ks] = *reinterpret_cast<const uint4 *>(p + 16 * ks);
         }
     }
 }
@@ -275,7 +243,6 @@ __device__ __forceinline__ void role_load_bc(const Ctx &c, Lds &L, int lane)
     };
     issue(tile_at(c, 0));
     SsmTile dpf = tile_at(c, 1);
-    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;  // == (s + 2) % 3: LDS buffer of tile k in a ring of three
         const int k = s + 2;
@@ -288,7 +255,6 @@ __device__ __forceinline__ void role_load_bc(const Ctx &c, Lds &L, int lane)
                 issue(dpf);
             dpf = tile_at(c, k + 2);
         }
-        SSM_TRACE(1);
     });
 }
 
@@ -312,7 +278,6 @@ __device__ __forceinline__ void role_load_x(const Ctx &c, Lds &L, int lane)
     };
     issue(tile_at(c, 0));
     SsmTile dpf = tile_at(c, 1);
-    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;  // == (s + 2) % 3
         const int k = s + 2;
@@ -346,7 +311,6 @@ __device__ __forceinline__ void role_load_x(const Ctx &c, Lds &L, int lane)
                 issue(dpf);
             dpf = tile_at(c, k + 2);
         }
-        SSM_TRACE(1);
     });
 }
 
@@ -360,7 +324,6 @@ __device__ __forceinline__ void role_load_x(const Ctx &c, Lds &L, int lane)
 __device__ __forceinline__ void role_offdiag(const Ctx &c, Lds &L, int lane)
 {
     const int i = lane & 31, q = lane >> 5;
-    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
         constexpr int b = (u + 2) % 3;  // == (s + 1) % 3
@@ -397,7 +360,6 @@ __device__ __forceinline__ void role_offdiag(const Ctx &c, Lds &L, int lane)
             L.M10[k & 1][lane][1] =
                 make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
         }
-        SSM_TRACE(1);
     });
 }
 
@@ -418,7 +380,6 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
         cf[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
         constexpr int b = (u + 1) % 3;   // == s % 3 for s >= 0
@@ -455,7 +416,6 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
                 fb[ks] = lds_frag(pb + 16 * ks);
             }
         }
-        SSM_TRACE(3);
         // Two independent MFMA chains back to back: first the diagonal score
         // block of tile s+1, then S.C of tile s.  The vector-ALU masking of the
         // first overlaps the matrix work of the second.
@@ -470,11 +430,9 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
             for (int ks = 0; ks < 8; ++ks)
                 Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], cf[ks], Y, 0, 0, 0);
         }
-        SSM_TRACE(4);
         uint4 gn0 = make_uint4(0, 0, 0, 0), gn1 = gn0;
         if (have_next)
             mask_diag(acc, L.tab[bn], 32 * IH, i, q, c.Dh, gn0, gn1);
-        SSM_TRACE(5);
         // ---- outputs of tile s ----
         if (s >= 0) {
             const SsmTile t = tile_at(c, s);
@@ -490,7 +448,6 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
             // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of
             // token i.  Through this wave's own LDS tile to token-major rows, then
             // 16 bytes per lane with four lanes per 64-byte row of y.
-            SSM_TRACE(6);
             bf16_t(*ys)[LDY] = L.Ys[IH];
 #pragma unroll
             for (int a = 0; a < 4; ++a)
@@ -506,7 +463,6 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
                                                8 * (lane & 3)) = o;
             }
         }
-        SSM_TRACE(7);
         // the scores part hands its C fragments and masked block to the next step
         if (have_next) {
             g0 = gn0;
@@ -515,7 +471,6 @@ __device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
             for (int ks = 0; ks < 8; ++ks)
                 cf[ks] = cn[ks];
         }
-        SSM_TRACE(1);
     });
 }
 
@@ -544,7 +499,6 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int s
     const int g4 = lane >> 4;
     const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-    SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         constexpr int u = decltype(U)::value;
         constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
@@ -584,7 +538,6 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int s
                             make_float4(S[t2][4 * a], S[t2][4 * a + 1], S[t2][4 * a + 2], S[t2][4 * a + 3]);
                 }
         }
-        SSM_TRACE(1);
     });
 }
 
