@@ -1,0 +1,138 @@
+// Driver of the CPU emulation of the scan kernels (test infrastructure only): reads a problem file, builds the plan
+// with the library's own plan code, runs the CPU-compiled scan kernel on fibers and writes y and the checkpoint
+// states.  Every buffer a kernel sees is an exact-size allocation flush against an inaccessible page.
+//   emu_main <in.bin> <out.bin> [order: 0 forward | 1 reverse | n>=2 shuffle seed] [end|start] [drop_barrier]
+//   "end"/"start": which end of each buffer touches the inaccessible page (overruns / underruns fault)
+//   drop_barrier: ordinal of one workgroup barrier that is made not to wait (self-test of the race check)
+#include <hip/hip_runtime.h>
+#include <sys/mman.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "device_utils.h"
+
+namespace emu {
+void set_order_mode(int m);
+void set_drop_barrier(long n);
+long switches();
+}  // namespace emu
+
+// exact-size allocation flush against an inaccessible page: any overrun faults at once
+static void *guarded(size_t bytes, bool end_aligned)
+{
+    const size_t page = 4096, span = (bytes + page - 1) / page * page + page;
+    unsigned char *m =
+        static_cast<unsigned char *>(mmap(nullptr, span + 2 * page, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0));
+    if (m == MAP_FAILED) {
+        perror("mmap");
+        exit(2);
+    }
+    mprotect(m, page, PROT_NONE);
+    mprotect(m + page + span, page, PROT_NONE);
+    if (!end_aligned)
+        return m + page;
+    return m + page + span - (bytes + 15) / 16 * 16;  // 16-byte alignment as device allocations have at least
+}
+
+template <typename T> static void read_vec(FILE *f, T *dst, size_t n)
+{
+    if (n && fread(dst, sizeof(T), n, f) != n) {
+        fprintf(stderr, "short read\n");
+        exit(2);
+    }
+}
+
+int main(int argc, char **argv)
+{
+    if (argc < 3) {
+        fprintf(stderr, "usage: emu_main in.bin out.bin [order] [end|start] [drop_barrier]\n");
+        return 2;
+    }
+    emu::set_order_mode(argc > 3 ? atoi(argv[3]) : 0);
+    const bool end_aligned = !(argc > 4 && argv[4][0] == 's');
+    if (argc > 5)
+        emu::set_drop_barrier(atol(argv[5]));
+    FILE *f = fopen(argv[1], "rb");
+    if (!f) {
+        perror(argv[1]);
+        return 2;
+    }
+    int32_t hdr[10];
+    read_vec(f, hdr, 10);
+    if (hdr[0] != 0x53534d31) {
+        fprintf(stderr, "bad magic\n");
+        return 2;
+    }
+    const int io = hdr[1], T = hdr[2], H = hdr[3], P = hdr[4], N = hdr[5], G = hdr[6], chunk = hdr[7], batch = hdr[8],
+              n_ckpt = hdr[9];
+    const size_t esz = io == 0 ? 4 : 2;
+    std::vector<int32_t> cu(batch + 1), cu_ck(batch + 1), ck(n_ckpt > 0 ? n_ckpt : 1), has_init(batch);
+    read_vec(f, cu.data(), batch + 1);
+    read_vec(f, cu_ck.data(), batch + 1);
+    read_vec(f, ck.data(), n_ckpt);
+    read_vec(f, has_init.data(), batch);
+    const size_t nx = (size_t)T * H * P, ndt = (size_t)T * H, nb = (size_t)T * G * N, nst = (size_t)H * P * N;
+    void *x = guarded(nx * esz, end_aligned), *dt = guarded(ndt * esz, end_aligned), *B = guarded(nb * esz, end_aligned),
+         *C = guarded(nb * esz, end_aligned);
+    float *A = static_cast<float *>(guarded(H * 4, end_aligned)), *D = static_cast<float *>(guarded(H * 4, end_aligned));
+    read_vec(f, static_cast<unsigned char *>(x), nx * esz);
+    read_vec(f, static_cast<unsigned char *>(dt), ndt * esz);
+    read_vec(f, static_cast<unsigned char *>(B), nb * esz);
+    read_vec(f, static_cast<unsigned char *>(C), nb * esz);
+    read_vec(f, A, H);
+    read_vec(f, D, H);
+    const float **init = static_cast<const float **>(guarded(sizeof(float *) * (batch ? batch : 1), end_aligned));
+    bool any_init = false;
+    for (int b = 0; b < batch; ++b) {
+        init[b] = nullptr;
+        if (has_init[b]) {
+            float *s = static_cast<float *>(guarded(nst * 4, end_aligned));
+            read_vec(f, s, nst);
+            init[b] = s;
+            any_init = true;
+        }
+    }
+    fclose(f);
+
+    ssm_shape_t shape;
+    shape.nheads = H, shape.headdim = P, shape.d_state = N, shape.ngroups = G, shape.chunk = chunk, shape.io_dtype = io;
+    ssm_plan_t *plan = nullptr;
+    int rc = ssm_plan_create(&shape, batch, cu.data(), cu_ck.data(), ck.data(), &plan);
+    if (rc != 0) {
+        fprintf(stderr, "ssm_plan_create: %d %s\n", rc, ssm_last_error());
+        return 2;
+    }
+    const size_t nt = plan->tiles.size();
+    SsmTile *tiles = static_cast<SsmTile *>(guarded(sizeof(SsmTile) * (nt ? nt : 1), end_aligned));
+    SsmSeq *seqs = static_cast<SsmSeq *>(guarded(sizeof(SsmSeq) * (batch ? batch : 1), end_aligned));
+    memcpy(tiles, plan->tiles.data(), sizeof(SsmTile) * nt);
+    memcpy(seqs, plan->seqs.data(), sizeof(SsmSeq) * batch);
+
+    void *y = guarded((nx ? nx : 1) * esz, end_aligned);
+    float *st = static_cast<float *>(guarded((size_t)(n_ckpt ? n_ckpt : 1) * nst * 4, end_aligned));
+    memset(y, 0xFF, nx * esz);                       // NaN patterns: every output must be overwritten
+    memset(st, 0xFF, (size_t)n_ckpt * nst * 4);
+
+    ScanArgs args;
+    args.x = x, args.dt = dt, args.A = A, args.B = B, args.C = C, args.D = D, args.y = y, args.state_out = st;
+    args.init_ptrs = any_init ? init : nullptr;
+    args.tiles = tiles, args.seqs = seqs;
+    args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
+    if (plan->n_workgroups > 0 && T > 0) {
+        const hipError_t e = plan->path == SSM_PATH_MFMA_BF16 ? launch_scan_mfma(plan, args, nullptr)
+                                                              : launch_scan_valu(plan, args, nullptr);
+        if (e != hipSuccess) {
+            fprintf(stderr, "launch failed\n");
+            return 2;
+        }
+    }
+    f = fopen(argv[2], "wb");
+    fwrite(y, esz, nx, f);
+    fwrite(st, 4, (size_t)n_ckpt * nst, f);
+    fclose(f);
+    printf("emu ok: path %d, %d workgroups, %zu tiles, %ld fiber switches\n", plan->path, plan->n_workgroups, nt,
+           emu::switches());
+    return 0;
+}

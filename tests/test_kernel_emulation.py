@@ -1,0 +1,196 @@
+"""The shipped scan kernels, compiled for the CPU and run on a SIMT emulator.
+
+No GPU is involved and nothing here is reachable from the library: the kernel
+sources of `paper_2411_19379_amd/csrc` are compiled as plain C++ against
+`tests/kernel_emu` (one fiber per lane; matrix-core products, LDS transpose
+reads, DPP shifts and lane reads evaluated per wave from the gfx950 operand
+layouts) and driven on seeded workloads.  Checked:
+
+* results against the fp64 oracle, to the tolerance of the storage type;
+* LDS ordering: between two workgroup barriers the emulator runs the waves one
+  after another in forward, reverse and shuffled order, and every order must
+  give bit-identical outputs (a read/write race between two waves cannot);
+* bounds: LDS and every global buffer sit flush against an inaccessible page,
+  once with the end and once with the start of the buffer at the page, so any
+  access outside a buffer kills the run; LDS and the outputs start as NaN
+  patterns, so a value read before it is written, or an output never written,
+  shows up as a non-finite result;
+* the checker itself: with one barrier made not to wait, the orders disagree.
+
+The only edits to the kernel sources are textual and listed in `_convert`: the
+two LDS-wait/barrier instructions become emulator calls and the dynamic LDS
+array becomes a pointer to the emulated LDS.
+"""
+from __future__ import annotations
+
+import os
+import re
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, rel_err
+from oracle import ssm_prefill_oracle
+from workloads import LayerShape, make_workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EMU = os.path.join(ROOT, "tests", "kernel_emu")
+CSRC = os.path.join(ROOT, "paper_2411_19379_amd", "csrc")
+CLANG = shutil.which("amdclang++") or "/opt/rocm/lib/llvm/bin/clang++"
+
+_SUBST = [
+    (r'asm volatile\("s_waitcnt lgkmcnt\(0\)\\n\\ts_barrier" ::: "memory"\);', "emu::barrier(__LINE__);"),
+    (r'asm volatile\("s_waitcnt lgkmcnt\(0\)" ::: "memory"\);', "emu::wave_sync(__LINE__);"),
+    (r"extern __shared__ __align__\(16\) unsigned char lds_raw\[\];", "unsigned char *lds_raw = emu::lds_base();"),
+]
+
+
+def _convert(src: str, dst: str) -> None:
+    text = open(src).read()
+    for pat, rep in _SUBST:
+        text = re.sub(pat, rep, text)
+    assert "asm volatile" not in text and "__shared__" not in text, f"{src}: construct the emulator does not know"
+    open(dst, "w").write(text)
+
+
+@pytest.fixture(scope="session")
+def emu_binary(tmp_path_factory):
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ with bf16 vector support found")
+    d = str(tmp_path_factory.mktemp("kernel_emu"))
+    _convert(os.path.join(CSRC, "scan_mfma.hip"), os.path.join(d, "scan_mfma.cpp"))
+    _convert(os.path.join(CSRC, "scan_valu.hip"), os.path.join(d, "scan_valu.cpp"))
+    flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
+             "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    srcs = [os.path.join(d, "scan_mfma.cpp"), os.path.join(d, "scan_valu.cpp"), os.path.join(CSRC, "plan.cpp"),
+            os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_main.cpp")]
+    objs = []
+    procs = []
+    for s in srcs:
+        o = os.path.join(d, os.path.basename(s) + ".o")
+        objs.append(o)
+        procs.append(subprocess.Popen([CLANG, *flags, "-c", s, "-o", o], stderr=subprocess.PIPE, text=True))
+    for p in procs:
+        _, err = p.communicate()
+        assert p.returncode == 0, err[-3000:]
+    out = os.path.join(d, "emu_main")
+    subprocess.run([CLANG, *objs, "-o", out], check=True)
+    return out
+
+
+def _write_problem(path, wl, init_states):
+    s = wl.shape
+    io = 0 if s.io_dtype == "f32" else 1
+    with open(path, "wb") as f:
+        np.asarray([0x53534D31, io, wl.total_tokens, s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, wl.batch,
+                    wl.n_ckpt], dtype=np.int32).tofile(f)
+        np.asarray(wl.cu_seqlens, dtype=np.int32).tofile(f)
+        np.asarray(wl.cu_ckpt(), dtype=np.int32).tofile(f)
+        np.asarray(wl.ckpt_flat(), dtype=np.int32)[: wl.n_ckpt].tofile(f)
+        np.asarray([0 if v is None else 1 for v in init_states], dtype=np.int32).tofile(f)
+        for t in (wl.inputs.x, wl.inputs.dt, wl.inputs.B, wl.inputs.C):
+            t = t.contiguous().cpu()
+            (t.view(torch.int16) if io else t).numpy().tofile(f)
+        wl.A.cpu().numpy().astype(np.float32).tofile(f)
+        wl.D.cpu().numpy().astype(np.float32).tofile(f)
+        for v in init_states:
+            if v is not None:
+                np.ascontiguousarray(v.cpu().numpy(), dtype=np.float32).tofile(f)
+
+
+def _read_result(path, wl):
+    s = wl.shape
+    nx = wl.total_tokens * s.nheads * s.headdim
+    raw = np.fromfile(path, dtype=np.uint8)
+    if s.io_dtype == "f32":
+        y = raw[: nx * 4].view(np.float32).astype(np.float64)
+        off = nx * 4
+    else:
+        y = torch.from_numpy(raw[: nx * 2].view(np.int16).copy()).view(torch.bfloat16).float().numpy().astype(np.float64)
+        off = nx * 2
+    st = raw[off:].view(np.float32).reshape(wl.n_ckpt, s.nheads, s.headdim, s.d_state)
+    return y.reshape(wl.total_tokens, s.nheads, s.headdim), st, raw
+
+
+def _emulate(binary, wl, init, tmp_path, order, align, drop=None):
+    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}.bin")
+    if not os.path.exists(pin):
+        _write_problem(pin, wl, init)
+    cmd = [binary, pin, pout, str(order), align] + ([str(drop)] if drop is not None else [])
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
+    return _read_result(pout, wl)
+
+
+def _oracle(wl, init):
+    return ssm_prefill_oracle(wl.inputs.x, wl.inputs.dt, wl.A, wl.inputs.B, wl.inputs.C, wl.D, wl.cu_seqlens,
+                              [None if v is None else v.cpu().numpy() for v in init], wl.ckpt_pos)
+
+
+def _with_empty_sequence(wl):
+    """Insert a zero-length sequence in the middle of the packed batch."""
+    wl.seqlens.insert(1, 0)
+    wl.cu_seqlens = np.concatenate([[0], np.cumsum(wl.seqlens)]).astype(np.int32)
+    wl.ckpt_pos.insert(1, [])
+    wl.init_kind.insert(1, "zeros")
+    wl.init_state.insert(1, None)
+    return wl
+
+
+# name: (H, P, N, G, chunk), configuration of the generator, its overrides
+CASES = {
+    # ragged packed batch: partial tiles, checkpoints inside tiles, sequences starting from a cached state
+    "ragged": ((2, 64, 128, 1, 64), 2, dict(batch=3, len_range=(1, 300))),
+    # one sequence over several tiles, periodic checkpoints, no checkpoint at the end
+    "long": ((2, 64, 128, 1, 64), 4, dict(seqlen=450, ckpt_every=100)),
+    # sequences shorter than any tile
+    "tiny": ((2, 64, 128, 1, 64), 2, dict(batch=2, len_range=(1, 3))),
+    # one 32-channel slice per head, several groups with several heads each, 32-token tiles
+    "p32_groups": ((4, 32, 128, 2, 32), 2, dict(batch=2, len_range=(20, 120))),
+    # four slices per head, large chunk
+    "p128": ((1, 128, 128, 1, 256), 4, dict(seqlen=200, ckpt_every=64)),
+    # shapes outside the matrix-core path (any storage type takes the fp32 vector kernel)
+    "odd": ((6, 24, 40, 3, 64), 2, dict(batch=4, len_range=(1, 90))),
+    # a zero-length sequence inside the batch
+    "empty_seq": ((2, 64, 128, 1, 64), 2, dict(batch=3, len_range=(30, 100))),
+}
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_emulated_kernel_matches_oracle_in_any_wave_order(emu_binary, tmp_path, io, case):
+    (H, P, N, G, chunk), cfg, kw = CASES[case]
+    if io == "f32" and P * N > 8192:
+        pytest.skip("the fp32 vector kernel holds at most 8192 state elements per head")
+    shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype=io)
+    wl = make_workload(cfg, "cpu", seed=11, shape=shape, **kw)
+    if case == "empty_seq":
+        wl = _with_empty_sequence(wl)
+    init = list(wl.init_state)
+    y_ref, st_ref = _oracle(wl, init)
+    first = None
+    for order, align in ((0, "end"), (1, "start"), (7, "end"), (12, "start")):
+        y, st, raw = _emulate(emu_binary, wl, init, tmp_path, order, align)
+        assert np.all(np.isfinite(y)) and np.all(np.isfinite(st)), "an output was never written, or LDS was read before written"
+        assert max(rel_err(y, y_ref)) <= TOL[io]
+        assert max(rel_err(st.astype(np.float64), st_ref)) <= TOL[io]
+        if first is None:
+            first = raw
+        assert np.array_equal(first, raw), f"wave order {order} changes the result: LDS race"
+
+
+def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
+    """Self-test of the race check on the bf16 kernel: with the barrier of one
+    pipeline step made not to wait, forward and reverse wave order disagree."""
+    shape = LayerShape(nheads=1, headdim=32, d_state=128, ngroups=1, chunk=64, io_dtype="bf16")
+    wl = make_workload(4, "cpu", seed=5, shape=shape, seqlen=450, ckpt_every=200)
+    init = list(wl.init_state)
+    ref = _emulate(emu_binary, wl, init, tmp_path, 0, "end")[2]
+    noticed = 0
+    for drop in (3, 4, 5):
+        outs = [_emulate(emu_binary, wl, init, tmp_path, order, "end", drop)[2] for order in (0, 1)]
+        noticed += not (np.array_equal(outs[0], ref) and np.array_equal(outs[1], ref))
+    assert noticed == 3
