@@ -13,6 +13,12 @@
 
 #include "device_utils.h"
 
+#ifdef SSM_EMU_CANDIDATE
+// the candidate revision of the matrix-core kernel (tests/kernel_emu/candidate) takes a workspace
+size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
+hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
+#endif
+
 namespace emu {
 void set_order_mode(int m);
 void set_drop_barrier(long n);
@@ -121,8 +127,20 @@ int main(int argc, char **argv)
     args.tiles = tiles, args.seqs = seqs;
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
     if (plan->n_workgroups > 0 && T > 0) {
+#ifdef SSM_EMU_CANDIDATE
+        hipError_t e;
+        if (plan->path == SSM_PATH_MFMA_BF16) {
+            const size_t ws_bytes = scan_mfma_next_workspace_bytes(plan);
+            void *ws = guarded(ws_bytes ? ws_bytes : 16, end_aligned);
+            memset(ws, 0xFF, ws_bytes);
+            e = launch_scan_mfma_next(plan, args, ws, nullptr);
+        } else {
+            e = launch_scan_valu(plan, args, nullptr);
+        }
+#else
         const hipError_t e = plan->path == SSM_PATH_MFMA_BF16 ? launch_scan_mfma(plan, args, nullptr)
                                                               : launch_scan_valu(plan, args, nullptr);
+#endif
         if (e != hipSuccess) {
             fprintf(stderr, "launch failed\n");
             return 2;
