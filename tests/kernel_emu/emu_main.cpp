@@ -3,7 +3,9 @@
 // states.  Every buffer a kernel sees is an exact-size allocation flush against an inaccessible page.
 //   emu_main <in.bin> <out.bin> [order: 0 forward | 1 reverse | n>=2 shuffle seed] [end|start] [drop_barrier]
 //   "end"/"start": which end of each buffer touches the inaccessible page (overruns / underruns fault)
-//   drop_barrier: ordinal of one workgroup barrier that is made not to wait (self-test of the race check)
+//   drop_barrier: ordinal of one workgroup barrier that is made not to wait (self-test of the race check; -1: none)
+//   a 6th argument "advance" (candidate build only) runs the roll-forward kernel instead: every sequence's state
+//   (its initial state, or zeros) is advanced in place, and the output holds y and then one state per sequence
 #include <hip/hip_runtime.h>
 #include <sys/mman.h>
 
@@ -17,6 +19,8 @@
 // the candidate revision of the matrix-core kernel (tests/kernel_emu/candidate) takes a workspace
 size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
 hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
+// the candidate roll-forward entry: states advanced in place
+hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, float *const *d_state_ptrs, hipStream_t stream);
 #endif
 
 namespace emu {
@@ -60,6 +64,7 @@ int main(int argc, char **argv)
     const bool end_aligned = !(argc > 4 && argv[4][0] == 's');
     if (argc > 5)
         emu::set_drop_barrier(atol(argv[5]));
+    const bool advance = argc > 6 && strcmp(argv[6], "advance") == 0;
     FILE *f = fopen(argv[1], "rb");
     if (!f) {
         perror(argv[1]);
@@ -126,6 +131,32 @@ int main(int argc, char **argv)
     args.init_ptrs = any_init ? init : nullptr;
     args.tiles = tiles, args.seqs = seqs;
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
+    if (advance) {
+#ifdef SSM_EMU_CANDIDATE
+        float **sp = static_cast<float **>(guarded(sizeof(float *) * (batch ? batch : 1), end_aligned));
+        for (int b = 0; b < batch; ++b) {
+            sp[b] = static_cast<float *>(guarded(nst * 4, end_aligned));
+            if (init[b])
+                memcpy(sp[b], init[b], nst * 4);
+            else
+                memset(sp[b], 0, nst * 4);
+        }
+        if (launch_state_advance(plan, args, sp, nullptr) != hipSuccess) {
+            fprintf(stderr, "launch_state_advance failed\n");
+            return 2;
+        }
+        f = fopen(argv[2], "wb");
+        fwrite(y, esz, nx, f);
+        for (int b = 0; b < batch; ++b)
+            fwrite(sp[b], 4, nst, f);
+        fclose(f);
+        printf("emu ok: advance, %d sequences, %ld fiber switches\n", batch, emu::switches());
+        return 0;
+#else
+        fprintf(stderr, "advance mode needs the candidate build\n");
+        return 2;
+#endif
+    }
     if (plan->n_workgroups > 0 && T > 0) {
 #ifdef SSM_EMU_CANDIDATE
         hipError_t e;

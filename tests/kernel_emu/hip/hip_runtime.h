@@ -32,6 +32,7 @@ struct dim3 {
 };
 typedef int hipError_t;
 constexpr hipError_t hipSuccess = 0;
+constexpr hipError_t hipErrorInvalidValue = 1;
 typedef void *hipStream_t;
 constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }

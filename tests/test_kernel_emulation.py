@@ -17,8 +17,9 @@ layouts) and driven on seeded workloads.  Checked:
   shows up as a non-finite result;
 * the checker itself: with one barrier made not to wait, the orders disagree.
 
-The same checks run on `tests/kernel_emu/candidate/scan_mfma_next.hip`, the next revision of the matrix-core
-kernel, which is not built into the library and has not run on a GPU yet.
+The same checks run on the candidates in `tests/kernel_emu/candidate/` (the next revision of the matrix-core
+kernel and a roll-forward kernel that advances cached states in place), which are not built into the library and
+have not run on a GPU yet.
 
 The only edits to the kernel sources are textual and listed in `_convert`: the
 two LDS-wait/barrier instructions become emulator calls and the dynamic LDS
@@ -59,7 +60,7 @@ def _convert(src: str, dst: str) -> None:
     open(dst, "w").write(text)
 
 
-def _build(tmp_path_factory, name, mfma_source, extra_flags=()):
+def _build(tmp_path_factory, name, mfma_source, extra_flags=(), extra_sources=()):
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ with bf16 vector support found")
     d = str(tmp_path_factory.mktemp(name))
@@ -69,6 +70,9 @@ def _build(tmp_path_factory, name, mfma_source, extra_flags=()):
              "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags]
     srcs = [os.path.join(d, "scan_mfma.cpp"), os.path.join(d, "scan_valu.cpp"), os.path.join(CSRC, "plan.cpp"),
             os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_main.cpp")]
+    for k, src in enumerate(extra_sources):
+        _convert(src, os.path.join(d, f"extra{k}.cpp"))
+        srcs.append(os.path.join(d, f"extra{k}.cpp"))
     objs = []
     procs = []
     for s in srcs:
@@ -93,7 +97,7 @@ def emu_binary(tmp_path_factory):
 def emu_candidate_binary(tmp_path_factory):
     """The candidate revision of the matrix-core kernel (not built into the library) beside the shipped fp32 one."""
     return _build(tmp_path_factory, "kernel_emu_candidate", os.path.join(EMU, "candidate", "scan_mfma_next.hip"),
-                  ["-DSSM_EMU_CANDIDATE"])
+                  ["-DSSM_EMU_CANDIDATE"], [os.path.join(EMU, "candidate", "state_advance.hip")])
 
 
 def _write_problem(path, wl, init_states):
@@ -116,7 +120,7 @@ def _write_problem(path, wl, init_states):
                 np.ascontiguousarray(v.cpu().numpy(), dtype=np.float32).tofile(f)
 
 
-def _read_result(path, wl):
+def _read_result(path, wl, n_states=None):
     s = wl.shape
     nx = wl.total_tokens * s.nheads * s.headdim
     raw = np.fromfile(path, dtype=np.uint8)
@@ -126,18 +130,23 @@ def _read_result(path, wl):
     else:
         y = torch.from_numpy(raw[: nx * 2].view(np.int16).copy()).view(torch.bfloat16).float().numpy().astype(np.float64)
         off = nx * 2
-    st = raw[off:].view(np.float32).reshape(wl.n_ckpt, s.nheads, s.headdim, s.d_state)
+    st = raw[off:].view(np.float32).reshape(wl.n_ckpt if n_states is None else n_states, s.nheads, s.headdim,
+                                            s.d_state)
     return y.reshape(wl.total_tokens, s.nheads, s.headdim), st, raw
 
 
-def _emulate(binary, wl, init, tmp_path, order, align, drop=None):
-    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}.bin")
+def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False):
+    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}.bin")
     if not os.path.exists(pin):
         _write_problem(pin, wl, init)
-    cmd = [binary, pin, pout, str(order), align] + ([str(drop)] if drop is not None else [])
+    cmd = [binary, pin, pout, str(order), align]
+    if drop is not None or advance:
+        cmd.append(str(-1 if drop is None else drop))
+    if advance:
+        cmd.append("advance")
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
-    return _read_result(pout, wl)
+    return _read_result(pout, wl, n_states=wl.batch if advance else None)
 
 
 def _oracle(wl, init):
@@ -206,6 +215,52 @@ def test_candidate_kernel_matches_oracle_in_any_wave_order(emu_candidate_binary,
     """The candidate carries the decay-weighted x as a bf16 pair, so its checkpoints are held to 1e-4 where it runs
     (the "odd" shape falls to the fp32 vector kernel as before)."""
     _check_case(emu_candidate_binary, tmp_path, "bf16", case, state_tol=1e-4)
+
+
+ADVANCE_CASES = {
+    # decode step: one token per sequence, some sequences with a cached state, some from zero
+    "decode": ((4, 64, 128, 2, 64), [1, 1, 1, 1, 1]),
+    # roll-forward by a few tokens, one sequence left alone (no tokens)
+    "roll": ((2, 64, 128, 1, 64), [17, 0, 3, 64]),
+    # small and unusual shapes: N = 16 (4 lanes per row), P not a multiple of the rows per pass
+    "small": ((4, 16, 16, 1, 64), [5, 2]),
+    "odd_p": ((3, 24, 64, 3, 16), [9, 33]),
+    "wide": ((1, 8, 256, 1, 64), [4]),
+}
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+@pytest.mark.parametrize("case", sorted(ADVANCE_CASES))
+def test_candidate_state_advance_matches_oracle(emu_candidate_binary, tmp_path, io, case):
+    """The roll-forward candidate: states advanced in place and y against the oracle started from the same states.
+    All arithmetic is fp32, so states are held to 1e-5 whatever the storage type; y carries its storage rounding."""
+    (H, P, N, G, chunk), seqlens = ADVANCE_CASES[case]
+    shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype=io)
+    wl = make_workload(2, "cpu", seed=23, shape=shape, batch=len(seqlens), len_range=(1, 2))
+    # impose the lengths of the case on the drawn batch (inputs are per token, so redraw them at the new total)
+    from workloads.gen import _gen, draw_layer_inputs
+    wl.seqlens = list(seqlens)
+    wl.cu_seqlens = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    wl.inputs = draw_layer_inputs(shape, int(sum(seqlens)), _gen("cpu", 77), "cpu")
+    wl.ckpt_pos = [[n] if n > 0 else [] for n in seqlens]  # the oracle's checkpoint = the state after the last token
+    init = list(wl.init_state)
+    y_ref, st_ref = _oracle(wl, init)
+    first = None
+    for order, align in ((0, "end"), (1, "start")):
+        y, st, raw = _emulate(emu_candidate_binary, wl, init, tmp_path, order, align, advance=True)
+        assert np.all(np.isfinite(y)) and np.all(np.isfinite(st))
+        assert max(rel_err(y, y_ref)) <= (5e-3 if io == "bf16" else 1e-5)
+        k = 0
+        for b, n in enumerate(seqlens):
+            if n == 0:  # untouched: still the initial state (or zeros)
+                want = np.zeros_like(st[b]) if init[b] is None else init[b].numpy()
+                assert np.array_equal(st[b], want)
+            else:
+                assert max(rel_err(st[b].astype(np.float64), st_ref[k])) <= 1e-5
+                k += 1
+        if first is None:
+            first = raw
+        assert np.array_equal(first, raw)
 
 
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
