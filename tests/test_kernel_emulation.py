@@ -94,6 +94,22 @@ def emu_binary(tmp_path_factory):
 
 
 @pytest.fixture(scope="session")
+def emu_conv_binary(tmp_path_factory):
+    """The convolution candidate with its own driver."""
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ with bf16 vector support found")
+    d = str(tmp_path_factory.mktemp("kernel_emu_conv"))
+    _convert(os.path.join(EMU, "candidate", "conv1d_prefill.hip"), os.path.join(d, "conv1d_prefill.cpp"))
+    flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
+             "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    srcs = [os.path.join(d, "conv1d_prefill.cpp"), os.path.join(CSRC, "plan.cpp"), os.path.join(EMU, "emu_rt.cpp"),
+            os.path.join(EMU, "emu_conv_main.cpp")]
+    out = os.path.join(d, "emu_conv_main")
+    subprocess.run([CLANG, *flags, *srcs, "-o", out], check=True, capture_output=True)
+    return out
+
+
+@pytest.fixture(scope="session")
 def emu_candidate_binary(tmp_path_factory):
     """The candidate revision of the matrix-core kernel (not built into the library) beside the shipped fp32 one."""
     return _build(tmp_path_factory, "kernel_emu_candidate", os.path.join(EMU, "candidate", "scan_mfma_next.hip"),
@@ -261,6 +277,69 @@ def test_candidate_state_advance_matches_oracle(emu_candidate_binary, tmp_path, 
         if first is None:
             first = raw
         assert np.array_equal(first, raw)
+
+
+CONV_CASES = {
+    # (H, P, N, G, chunk) of the layer whose x, B and C pass through the convolution; sequence lengths; checkpoints
+    "ragged": ((2, 64, 128, 1, 64), [79, 0, 1, 130], [[37, 79], [], [1], [2, 64, 65, 130]]),
+    "short": ((1, 32, 128, 1, 64), [1, 2, 3], [[1], [1, 2], [3]]),
+    "small_f32_tiles": ((4, 16, 16, 1, 64), [40, 21], [[5, 40], []]),
+}
+
+
+@pytest.mark.parametrize("K", [1, 2, 4])
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+@pytest.mark.parametrize("case", sorted(CONV_CASES))
+def test_candidate_conv1d_matches_oracle(emu_conv_binary, tmp_path, io, case, K):
+    """Outputs against the convolution oracle from the same cached states; checkpointed states are copies of
+    inputs and must be bit-exact."""
+    from oracle import conv1d_prefill_oracle
+    (H, P, N, G, chunk), seqlens, ckpts = CONV_CASES[case]
+    if io == "f32" and P * N > 8192:
+        pytest.skip("no fp32 plan for this layer shape")
+    C = H * P + 2 * G * N
+    T = int(sum(seqlens))
+    g = torch.Generator().manual_seed(1234 + K)
+    tdt = torch.float32 if io == "f32" else torch.bfloat16
+    xin = torch.randn((T, C), generator=g).to(tdt)
+    w = (torch.randn((C, K), generator=g) / K ** 0.5).float()
+    bias = torch.randn((C,), generator=g).float()
+    init = [torch.randn((C, K), generator=g).to(tdt) if (n > 0 and b % 2 == 0) else None for b, n in enumerate(seqlens)]
+    cu = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    cu_ck = np.concatenate([[0], np.cumsum([len(c) for c in ckpts])]).astype(np.int32)
+    flat = np.asarray([p for c in ckpts for p in c], dtype=np.int32)
+    out_ref, st_ref = conv1d_prefill_oracle(xin, w, bias, cu, init, ckpts, silu=True)
+
+    pin = str(tmp_path / "in.bin")
+    raw = (lambda t: t.contiguous().view(torch.int16).numpy()) if io == "bf16" else (lambda t: t.contiguous().numpy())
+    with open(pin, "wb") as f:
+        np.asarray([0x434F4E56, 0 if io == "f32" else 1, T, H, P, N, G, chunk, len(seqlens), len(flat), K, 1, 1],
+                   dtype=np.int32).tofile(f)
+        cu.tofile(f), cu_ck.tofile(f), flat.tofile(f)
+        np.asarray([0 if v is None else 1 for v in init], dtype=np.int32).tofile(f)
+        raw(xin).tofile(f), w.numpy().tofile(f), bias.numpy().tofile(f)
+        for v in init:
+            if v is not None:
+                raw(v).tofile(f)
+    first = None
+    for order, align in ((0, "end"), (1, "start")):
+        pout = str(tmp_path / f"out_{order}.bin")
+        r = subprocess.run([emu_conv_binary, pin, pout, str(order), align], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
+        got = np.fromfile(pout, dtype=np.uint8)
+        esz = 4 if io == "f32" else 2
+        def dec(b):
+            if io == "f32":
+                return b.view(np.float32).astype(np.float64)
+            return torch.from_numpy(b.view(np.int16).copy()).view(torch.bfloat16).float().numpy().astype(np.float64)
+        out = dec(got[: T * C * esz]).reshape(T, C)
+        st = dec(got[T * C * esz:]).reshape(len(flat), C, K)
+        assert np.all(np.isfinite(out)) and np.all(np.isfinite(st))
+        assert max(rel_err(out, out_ref)) <= (5e-3 if io == "bf16" else 1e-5)
+        assert np.array_equal(st, st_ref), "a checkpointed state is not the last K inputs"
+        if first is None:
+            first = got
+        assert np.array_equal(first, got)
 
 
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
