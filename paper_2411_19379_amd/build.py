@@ -1,4 +1,4 @@
-"""Build the HIP library (gfx950) in-tree with hipcc."""
+"""Build the HIP library (gfx950) in-tree with hipcc, and the host-only prefix-cache library with g++."""
 from __future__ import annotations
 
 import os
@@ -28,5 +28,19 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+CACHE_LIB_PATH = os.path.join(_PKG, "libprefix_cache.so")
+
+
+def build_prefix_cache(verbose: bool = False) -> str:
+    """The radix-tree bookkeeping is plain host C++: its own library, no GPU code, no dependency on the HIP one."""
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra", "-ffp-contract=off",
+           "-I", os.path.join(_ROOT, "include"), "-o", CACHE_LIB_PATH, os.path.join(CSRC, "prefix_cache.cpp")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return CACHE_LIB_PATH
+
+
 if __name__ == "__main__":
     build_library(verbose=True)
+    build_prefix_cache(verbose=True)
