@@ -21,3 +21,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _libraries_are_built():
+    """Tests load the libraries that are built; whatever is missing is built once, in-tree, before the first test."""
+    from paper_2411_19379_amd import build as b
+    if not os.path.exists(b.LIB_PATH):
+        b.build_library()
+    if not os.path.exists(b.CACHE_LIB_PATH):
+        b.build_prefix_cache()
