@@ -78,6 +78,9 @@ constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_XS_SPLIT
 #define SSM_XS_SPLIT 1  // 1: the decay-weighted x enters the state update as a bf16 pair (value, rounding remainder)
 #endif
+#ifndef SSM_SS_SPLIT
+#define SSM_SS_SPLIT 0  // 1: the copy of S used for S.C is a bf16 pair too (y after a resume from a large cached state)
+#endif
 #ifndef SSM_LDBS_PAD
 #define SSM_LDBS_PAD 8
 #endif
@@ -106,6 +109,9 @@ struct Lds {
     bf16_t Xl[2][kQ][LDX];        // what bf16 rounding took away from Xs
 #endif
     bf16_t Ss[2][kPW][LDB];       // bf16 copy of the running state, channel major
+#if SSM_SS_SPLIT
+    bf16_t Sl[2][kPW][LDB];       // what bf16 rounding took away from Ss
+#endif
     uint4 Md[2][2][64][2];        // [half][parity] masked diagonal score block as the output lane's two MFMA operands
     uint4 M10[2][64][2];          // off-diagonal score block, same form
     bf16_t Ys[2][kQ / 2][LDY];    // y of one token half on its way to coalesced stores
@@ -493,6 +499,18 @@ __device__ __forceinline__ void role_scores(const Ctx &c, Lds &L, int lane)
     });
 }
 
+// bf16 copy of four neighbouring state values (and, if asked for, of what the rounding took away)
+__device__ __forceinline__ void store_state_copy(Lds &L, int buf, int p, int n0, float v0, float v1, float v2, float v3)
+{
+    const uint32_t h0 = pack2(v0, v1), h1 = pack2(v2, v3);
+    *reinterpret_cast<uint2 *>(&L.Ss[buf][p][n0]) = make_uint2(h0, h1);
+#if SSM_SS_SPLIT
+    *reinterpret_cast<uint2 *>(&L.Sl[buf][p][n0]) =
+        make_uint2(pack2(v0 - __uint_as_float(h0 << 16), v1 - __uint_as_float(h0 & 0xffff0000u)),
+                   pack2(v2 - __uint_as_float(h1 << 16), v3 - __uint_as_float(h1 & 0xffff0000u)));
+#endif
+}
+
 // ---------------------------------------------------------------- outputs of tile k, token half IH
 template <int IH>
 __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
@@ -519,6 +537,13 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
                 fs[ks] = lds_frag(ps + 16 * ks);
                 fc[ks] = lds_frag(pc + 16 * ks);
             }
+#if SSM_SS_SPLIT
+            const bf16_t *pl = &L.Sl[(s + 1) & 1][i][8 * q];
+            bf16x8 fsl[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                fsl[ks] = lds_frag(pl + 16 * ks);
+#endif
             const uint4 g0 = L.Md[IH][s & 1][lane][0], g1 = L.Md[IH][s & 1][lane][1];
             const bf16_t *px = &L.Xr[s & 1][32 * IH + tr_row][tr_col];
             const bf16x8 x0 = lds_frag_tr(px, px + 8 * LDX), x1 = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
@@ -537,6 +562,11 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
                 Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], fc[ks], Y, 0, 0, 0);
+#if SSM_SS_SPLIT
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fsl[ks], fc[ks], Y, 0, 0, 0);
+#endif
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 Y[r] *= ei;
@@ -588,7 +618,7 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane)
             S[nb][4 * a + 1] = v.y;
             S[nb][4 * a + 2] = v.z;
             S[nb][4 * a + 3] = v.w;
-            *reinterpret_cast<uint2 *>(&L.Ss[1][p][n0]) = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
+            store_state_copy(L, 1, p, n0, v.x, v.y, v.z, v.w);
         }
     }
     // transpose reads, natural token order: group g4 covers row/column block
@@ -645,8 +675,7 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     const int n0 = 32 * (NS * SQ + nb) + 8 * a + 4 * q;
-                    *reinterpret_cast<uint2 *>(&L.Ss[s & 1][p][n0]) =
-                        make_uint2(pack2(S[nb][4 * a], S[nb][4 * a + 1]), pack2(S[nb][4 * a + 2], S[nb][4 * a + 3]));
+                    store_state_copy(L, s & 1, p, n0, S[nb][4 * a], S[nb][4 * a + 1], S[nb][4 * a + 2], S[nb][4 * a + 3]);
                 }
             if (t.ckpt_slot >= 0) {
 #pragma unroll
