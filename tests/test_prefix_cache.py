@@ -194,3 +194,34 @@ def test_retrospective_alpha_matches_the_oracle():
     assert chosen_at == idx_ref
     assert ad.rates == rates_ref
     assert ad.cache.config.alpha == a_ref
+
+
+def test_flop_aware_eviction_keeps_long_shared_prefixes():
+    """Section 4.2 / 5.3: under contention LRU lets many short, recent, never-reused entries push out the states of
+    long shared prefixes; the FLOP-aware score keeps them.  Small version against the oracle (same decisions), full
+    version for the size of the effect."""
+    from workloads.traces import make_mixed_trace
+    small = make_mixed_trace(2, n_docs=4, doc_len=(150, 400), n_requests=160, chat_len=(5, 40), q_len=(3, 10),
+                             out_len=(2, 12), vocab=500)
+    mc = ModelCost(**M7B)
+    probe = CacheOracle(mc, 10 ** 18, 0.0)
+    oracle_replay(probe, small)
+    cap = int(probe.used_bytes() * 0.08)
+    rates = {}
+    for alpha in (0.0, 2.0):
+        o, c = both(cap, alpha)
+        log_o, rate_o = oracle_replay(o, small)
+        log_c, rate_c = pc.replay(c, small)
+        assert log_c == log_o and rate_c == rate_o
+        rates[alpha] = rate_c
+    assert rates[2.0] > rates[0.0]
+
+    full = make_mixed_trace(1)
+    big = pc.PrefixCache(capacity_bytes=10 ** 18, alpha=0.0, **M7B)
+    _, best = pc.replay(big, full)
+    cap = int(big.stats().used_bytes * 0.05)
+    got = {}
+    for alpha in (0.0, 2.0):
+        c = pc.PrefixCache(capacity_bytes=cap, alpha=alpha, **M7B)
+        _, got[alpha] = pc.replay(c, full)
+    assert got[2.0] >= 1.5 * got[0.0] and got[2.0] <= best + 1e-12

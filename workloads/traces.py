@@ -42,3 +42,21 @@ def make_trace(seed: int, n_sessions: int = 12, n_prompts: int = 3, prompt_len=(
         if cursors[i] == len(sessions[i]):
             live.remove(i)
     return trace
+
+
+def make_mixed_trace(seed: int, n_docs: int = 6, doc_len=(3000, 9000), n_requests: int = 1500, p_doc: float = 0.25,
+                     chat_len=(50, 600), q_len=(20, 100), out_len=(20, 200),
+                     vocab: int = 32000) -> List[Tuple[List[int], List[int]]]:
+    """Long shared documents queried again and again (the "purely input" prefixes of Section 4.1: long-document QA,
+    few-shot prompts) among many short one-off chats that are never reused: the mix in which recency alone throws
+    away the entries that save the most compute per byte (Section 4.2)."""
+    rs = np.random.RandomState(seed)
+    docs = [list(map(int, rs.randint(0, vocab, size=rs.randint(doc_len[0], doc_len[1] + 1)))) for _ in range(n_docs)]
+    trace = []
+    for _ in range(n_requests):
+        if rs.rand() < p_doc:
+            inp = docs[rs.randint(n_docs)] + list(map(int, rs.randint(0, vocab, size=rs.randint(q_len[0], q_len[1] + 1))))
+        else:
+            inp = list(map(int, rs.randint(0, vocab, size=rs.randint(chat_len[0], chat_len[1] + 1))))
+        trace.append((inp, list(map(int, rs.randint(0, vocab, size=rs.randint(out_len[0], out_len[1] + 1))))))
+    return trace
