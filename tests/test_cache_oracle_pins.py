@@ -141,3 +141,21 @@ def test_token_hit_rate_of_a_replayed_trace():
     log, rate = replay(c, trace)
     assert [r[0] for r in log] == [0, 5, 8]
     assert rate == pytest.approx(13 / 20)
+
+
+def test_flop_efficiency_grows_faster_with_more_ssm_layers():
+    """Section 4.2, figure on FLOP efficiency of 7B models: FLOPs saved per byte of all states (Eq. 1) grows with
+    the sequence length, and the more SSM layers the model has the steeper; for attention-only it is near-constant
+    relative to its size (L + 2D plus the MLP share)."""
+    models = {"transformer": ModelCost(32, 0, 32, 4096, 128), "hybrid": ModelCost(4, 24, 28, 4096, 128),
+              "mamba": ModelCost(0, 64, 0, 4096, 128)}
+
+    def eff(m, L):
+        return m.flops(L) / (m.kv_bytes_per_token * L + (m.ssm_bytes_per_state if m.n_ssm else 0))
+
+    slopes = {k: (eff(m, 32768) - eff(m, 1024)) / (32768 - 1024) for k, m in models.items()}
+    assert slopes["mamba"] > slopes["hybrid"] > slopes["transformer"] > 0
+    # attention-only: L + 2D from the attention layers plus 4D from the MLPs, i.e. it only doubles over 16K tokens,
+    # while the SSM-only model's grows in proportion to L
+    assert eff(models["transformer"], 16384) / eff(models["transformer"], 1) < 2.1
+    assert eff(models["mamba"], 16384) / eff(models["mamba"], 1) == pytest.approx(16384, rel=1e-6)
