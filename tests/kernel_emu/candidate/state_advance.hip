@@ -3,7 +3,8 @@
 //
 // Roll-forward of cached states (Section 4.1: a kernel that rolls a checkpointed state forward by a few tokens to
 // reach an exact position; with one token per sequence it is the decode step).  Every sequence of the batch brings
-// its own fp32 [H,P,N] state, which is advanced IN PLACE by the sequence's tokens with the token recurrence itself,
+// its own [H,P,N] state (fp32, or fp16 / bf16 as a cache stores it), which is advanced IN PLACE by the sequence's
+// tokens with the token recurrence itself,
 //
 //     a = exp(dt A),   S[p,n] = a S[p,n] + (dt x[p]) B[n],   y[p] = sum_n C[n] S[p,n] + D x[p],
 //
@@ -60,11 +61,45 @@ template <> struct Vec4<bf16_t> {
     }
 };
 
+// Storage type of the cached states: fp32, or fp16 / bf16 as a cache keeps them (Section 5.1: FP16 everywhere;
+// Appendix A.1: 2 bytes per state element), which halves the bytes this kernel moves.  Arithmetic stays fp32; a
+// reduced-precision state is rounded once, to nearest even, when it is written back.
+enum { ADV_STATE_F32 = 0, ADV_STATE_F16 = 1, ADV_STATE_BF16 = 2 };
+template <int ST> struct StateVec;
+template <> struct StateVec<ADV_STATE_F32> {
+    typedef float elem;
+    static __device__ __forceinline__ float4 load(const elem *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ __forceinline__ void store(elem *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+};
+template <> struct StateVec<ADV_STATE_F16> {
+    typedef _Float16 elem;
+    typedef __attribute__((ext_vector_type(4))) _Float16 h4;
+    static __device__ __forceinline__ float4 load(const elem *p)
+    {
+        const h4 h = *reinterpret_cast<const h4 *>(p);
+        return make_float4((float)h[0], (float)h[1], (float)h[2], (float)h[3]);
+    }
+    static __device__ __forceinline__ void store(elem *p, float4 v)
+    {
+        const h4 h = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+        *reinterpret_cast<h4 *>(p) = h;
+    }
+};
+template <> struct StateVec<ADV_STATE_BF16> {
+    typedef bf16_t elem;
+    static __device__ __forceinline__ float4 load(const elem *p) { return Vec4<bf16_t>::load(p); }
+    static __device__ __forceinline__ void store(elem *p, float4 v)
+    {
+        *reinterpret_cast<uint2 *>(p) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                                                   (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+    }
+};
+
 struct AdvanceArgs {
     const void *x, *dt, *B, *C;
     const float *A, *D;
     void *y;                   // may be null
-    float *const *state_ptrs;  // [batch] device pointers, each fp32 [H,P,N]; null = leave the sequence alone
+    void *const *state_ptrs;   // [batch] device pointers, each [H,P,N] in the state type; null = leave the sequence alone
     const SsmTile *tiles;
     const SsmSeq *seqs;
     int H, P, N, G;
@@ -72,9 +107,10 @@ struct AdvanceArgs {
     int slices;                // workgroups per (sequence, head)
 };
 
-template <typename IO, int LPR>
+template <typename IO, int LPR, int ST>
 __global__ __launch_bounds__(kAdvThreads) void ssm_advance_kernel(AdvanceArgs a)
 {
+    typedef typename StateVec<ST>::elem state_t;
     constexpr int kRowsPerPass = kAdvThreads / LPR;
     const int H = a.H, P = a.P, N = a.N, G = a.G;
     const int slice = blockIdx.x % a.slices;
@@ -87,7 +123,7 @@ __global__ __launch_bounds__(kAdvThreads) void ssm_advance_kernel(AdvanceArgs a)
     const int p_first = slice * kRowsPerPass * R + rs;  // rows p_first + kRowsPerPass * r
 
     const SsmSeq sq = a.seqs[seq];
-    float *state = a.state_ptrs[seq];
+    state_t *state = static_cast<state_t *>(a.state_ptrs[seq]);
     if (sq.tile_end <= sq.tile_begin || state == nullptr)
         return;  // nothing to advance; the whole workgroup leaves
 
@@ -105,7 +141,7 @@ __global__ __launch_bounds__(kAdvThreads) void ssm_advance_kernel(AdvanceArgs a)
         const int p = p_first + kRowsPerPass * r;
         S[r] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (r < R && p < P)
-            S[r] = *reinterpret_cast<const float4 *>(state + ((size_t)h * P + p) * N + 4 * c);
+            S[r] = StateVec<ST>::load(state + ((size_t)h * P + p) * N + 4 * c);
     }
 
     for (int ti = sq.tile_begin; ti < sq.tile_end; ++ti) {
@@ -141,19 +177,23 @@ __global__ __launch_bounds__(kAdvThreads) void ssm_advance_kernel(AdvanceArgs a)
     for (int r = 0; r < kAdvMaxRows; ++r) {
         const int p = p_first + kRowsPerPass * r;
         if (r < R && p < P)
-            *reinterpret_cast<float4 *>(state + ((size_t)h * P + p) * N + 4 * c) = S[r];
+            StateVec<ST>::store(state + ((size_t)h * P + p) * N + 4 * c, S[r]);
     }
 }
 
 template <typename IO, int LPR>
-void launch_lpr(const AdvanceArgs &a, int batch, hipStream_t stream)
+void launch_lpr(const AdvanceArgs &a, int batch, int state_type, hipStream_t stream)
 {
-    hipLaunchKernelGGL((ssm_advance_kernel<IO, LPR>), dim3((unsigned)(batch * a.H * a.slices)), dim3(kAdvThreads), 0,
-                       stream, a);
+    const dim3 grid((unsigned)(batch * a.H * a.slices)), block(kAdvThreads);
+    switch (state_type) {
+    case ADV_STATE_F16: hipLaunchKernelGGL((ssm_advance_kernel<IO, LPR, ADV_STATE_F16>), grid, block, 0, stream, a); break;
+    case ADV_STATE_BF16: hipLaunchKernelGGL((ssm_advance_kernel<IO, LPR, ADV_STATE_BF16>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((ssm_advance_kernel<IO, LPR, ADV_STATE_F32>), grid, block, 0, stream, a); break;
+    }
 }
 
 template <typename IO>
-hipError_t launch_io(AdvanceArgs &a, int batch, hipStream_t stream)
+hipError_t launch_io(AdvanceArgs &a, int batch, int state_type, hipStream_t stream)
 {
     const int lpr = a.N / 4;
     const int rows_per_pass = kAdvThreads / lpr;
@@ -163,13 +203,13 @@ hipError_t launch_io(AdvanceArgs &a, int batch, hipStream_t stream)
     a.rows_per_thread = R;
     a.slices = (a.P + rows_per_pass * R - 1) / (rows_per_pass * R);
     switch (lpr) {
-    case 1: launch_lpr<IO, 1>(a, batch, stream); break;
-    case 2: launch_lpr<IO, 2>(a, batch, stream); break;
-    case 4: launch_lpr<IO, 4>(a, batch, stream); break;
-    case 8: launch_lpr<IO, 8>(a, batch, stream); break;
-    case 16: launch_lpr<IO, 16>(a, batch, stream); break;
-    case 32: launch_lpr<IO, 32>(a, batch, stream); break;
-    case 64: launch_lpr<IO, 64>(a, batch, stream); break;
+    case 1: launch_lpr<IO, 1>(a, batch, state_type, stream); break;
+    case 2: launch_lpr<IO, 2>(a, batch, state_type, stream); break;
+    case 4: launch_lpr<IO, 4>(a, batch, state_type, stream); break;
+    case 8: launch_lpr<IO, 8>(a, batch, state_type, stream); break;
+    case 16: launch_lpr<IO, 16>(a, batch, state_type, stream); break;
+    case 32: launch_lpr<IO, 32>(a, batch, state_type, stream); break;
+    case 64: launch_lpr<IO, 64>(a, batch, state_type, stream); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -185,11 +225,12 @@ bool state_advance_supports(const ssm_shape_t &s)
 }
 
 // Advance the state of every sequence of the plan in place by the sequence's tokens; `d_state_ptrs` is a device array
-// of plan->batch device pointers.  y may be null.  Checkpoints of the plan are ignored (the result is the in-place
-// state after the last token).
-hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, float *const *d_state_ptrs, hipStream_t stream)
+// of plan->batch device pointers to states of type `state_type` (0 fp32, 1 fp16, 2 bf16).  y may be null.
+// Checkpoints of the plan are ignored (the result is the in-place state after the last token).
+hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs, int state_type,
+                                hipStream_t stream)
 {
-    if (!state_advance_supports(plan->shape))
+    if (!state_advance_supports(plan->shape) || state_type < ADV_STATE_F32 || state_type > ADV_STATE_BF16)
         return hipErrorInvalidValue;
     if (plan->batch == 0 || plan->tiles.empty())
         return hipSuccess;
@@ -208,6 +249,6 @@ hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, floa
     a.P = args.P;
     a.N = args.N;
     a.G = args.G;
-    return plan->shape.io_dtype == SSM_DT_F32 ? launch_io<float>(a, plan->batch, stream)
-                                              : launch_io<bf16_t>(a, plan->batch, stream);
+    return plan->shape.io_dtype == SSM_DT_F32 ? launch_io<float>(a, plan->batch, state_type, stream)
+                                              : launch_io<bf16_t>(a, plan->batch, state_type, stream);
 }

@@ -5,7 +5,8 @@
 //   "end"/"start": which end of each buffer touches the inaccessible page (overruns / underruns fault)
 //   drop_barrier: ordinal of one workgroup barrier that is made not to wait (self-test of the race check; -1: none)
 //   a 6th argument "advance" (candidate build only) runs the roll-forward kernel instead: every sequence's state
-//   (its initial state, or zeros) is advanced in place, and the output holds y and then one state per sequence
+//   (its initial state, or zeros) is advanced in place, and the output holds y and then one state per sequence;
+//   a 7th argument f16 or bf16 keeps the states in that type (converted from and to fp32 around the run)
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -18,7 +19,8 @@
 size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
 hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
 // the candidate roll-forward entry: states advanced in place
-hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, float *const *d_state_ptrs, hipStream_t stream);
+hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs, int state_type,
+                                hipStream_t stream);
 #endif
 
 namespace emu {
@@ -108,22 +110,35 @@ int main(int argc, char **argv)
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
     if (advance) {
 #ifdef SSM_EMU_CANDIDATE
-        float **sp = static_cast<float **>(guarded(sizeof(float *) * (batch ? batch : 1), end_aligned));
+        const int st_type = argc > 7 ? (strcmp(argv[7], "f16") == 0 ? 1 : strcmp(argv[7], "bf16") == 0 ? 2 : 0) : 0;
+        const size_t st_esz = st_type == 0 ? 4 : 2;
+        void **sp = static_cast<void **>(guarded(sizeof(void *) * (batch ? batch : 1), end_aligned));
         for (int b = 0; b < batch; ++b) {
-            sp[b] = static_cast<float *>(guarded(nst * 4, end_aligned));
-            if (init[b])
-                memcpy(sp[b], init[b], nst * 4);
-            else
-                memset(sp[b], 0, nst * 4);
+            sp[b] = guarded(nst * st_esz, end_aligned);
+            for (size_t e = 0; e < nst; ++e) {
+                const float v = init[b] ? init[b][e] : 0.f;
+                if (st_type == 0)
+                    static_cast<float *>(sp[b])[e] = v;
+                else if (st_type == 1)
+                    static_cast<_Float16 *>(sp[b])[e] = (_Float16)v;
+                else
+                    static_cast<bf16_t *>(sp[b])[e] = f32_to_bf16(v);
+            }
         }
-        if (launch_state_advance(plan, args, sp, nullptr) != hipSuccess) {
+        if (launch_state_advance(plan, args, sp, st_type, nullptr) != hipSuccess) {
             fprintf(stderr, "launch_state_advance failed\n");
             return 2;
         }
         f = fopen(argv[2], "wb");
         fwrite(y, esz, nx, f);
-        for (int b = 0; b < batch; ++b)
-            fwrite(sp[b], 4, nst, f);
+        std::vector<float> back(nst);
+        for (int b = 0; b < batch; ++b) {
+            for (size_t e = 0; e < nst; ++e)
+                back[e] = st_type == 0   ? static_cast<float *>(sp[b])[e]
+                          : st_type == 1 ? (float)static_cast<_Float16 *>(sp[b])[e]
+                                         : bf16_to_f32(static_cast<bf16_t *>(sp[b])[e]);
+            fwrite(back.data(), 4, nst, f);
+        }
         fclose(f);
         printf("emu ok: advance, %d sequences, %ld fiber switches\n", batch, emu::switches());
         return 0;

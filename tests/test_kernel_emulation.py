@@ -151,8 +151,8 @@ def _read_result(path, wl, n_states=None):
     return y.reshape(wl.total_tokens, s.nheads, s.headdim), st, raw
 
 
-def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False):
-    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}.bin")
+def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False, state_type=None):
+    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}_{state_type}.bin")
     if not os.path.exists(pin):
         _write_problem(pin, wl, init)
     cmd = [binary, pin, pout, str(order), align]
@@ -160,6 +160,8 @@ def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False)
         cmd.append(str(-1 if drop is None else drop))
     if advance:
         cmd.append("advance")
+        if state_type:
+            cmd.append(state_type)
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
     return _read_result(pout, wl, n_states=wl.batch if advance else None)
@@ -354,6 +356,37 @@ def test_candidate_conv1d_matches_oracle(emu_conv_binary, tmp_path, io, case, K)
         if first is None:
             first = got
         assert np.array_equal(first, got)
+
+
+@pytest.mark.parametrize("state_type,ulp", [("f16", 2.0 ** -10), ("bf16", 2.0 ** -7)])
+def test_candidate_state_advance_with_reduced_precision_states(emu_candidate_binary, tmp_path, state_type, ulp):
+    """States kept as a cache stores them (Section 5.1: FP16): read, advanced in fp32, rounded once on the way back.
+    Expected: the oracle's state from the same (representable) start, to one unit in the last place of the type."""
+    (H, P, N, G, chunk), seqlens = (4, 64, 128, 2, 64), [1, 7, 0, 2]
+    shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype="bf16")
+    wl = make_workload(2, "cpu", seed=29, shape=shape, batch=len(seqlens), len_range=(1, 2))
+    from workloads.gen import _gen, draw_layer_inputs
+    wl.seqlens = list(seqlens)
+    wl.cu_seqlens = np.concatenate([[0], np.cumsum(seqlens)]).astype(np.int32)
+    wl.inputs = draw_layer_inputs(shape, int(sum(seqlens)), _gen("cpu", 78), "cpu")
+    wl.ckpt_pos = [[n] if n > 0 else [] for n in seqlens]
+    tdt = torch.float16 if state_type == "f16" else torch.bfloat16
+    init = [None if v is None else v.to(tdt).float() for v in wl.init_state]   # representable starts
+    wl.init_state = init
+    y_ref, st_ref = _oracle(wl, init)
+    y, st, _ = _emulate(emu_candidate_binary, wl, init, tmp_path, 0, "end", advance=True, state_type=state_type)
+    assert max(rel_err(y, y_ref)) <= 5e-3
+    k = 0
+    for b, n in enumerate(seqlens):
+        if n == 0:
+            want = np.zeros_like(st[b]) if init[b] is None else init[b].numpy()
+            assert np.array_equal(st[b], want)
+        else:
+            ref = st_ref[k]
+            assert np.all(np.abs(st[b] - ref) <= ulp * np.maximum(np.abs(ref), 2.0 ** -14))
+            # and the stored values are values of the type
+            assert np.array_equal(torch.from_numpy(st[b].copy()).to(tdt).float().numpy(), st[b])
+            k += 1
 
 
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
