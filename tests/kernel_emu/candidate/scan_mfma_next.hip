@@ -197,10 +197,11 @@ struct Ctx {
     const bf16_t *__restrict__ Bg;
     const bf16_t *__restrict__ Cg;
     bf16_t *__restrict__ y;
-    float *__restrict__ state_out;
+    void *__restrict__ state_out;  // checkpoints, [slot][H][P][N] in the state type
     const float *__restrict__ cb;  // raw score blocks, [tile][group][3][16 x 64 lanes] fp32
     const SsmTile *__restrict__ tiles;
-    const float *init;  // this sequence's initial state or nullptr
+    const void *init;   // this sequence's initial state (state type) or nullptr
+    int state_type;     // 0 fp32, 1 fp16, 2 bf16: how cached states are stored; the running state is fp32
     int H, P, G, h, g, pbase;
     int tile_begin, n_tiles;
     float Ah, Dh;
@@ -499,6 +500,35 @@ __device__ __forceinline__ void role_scores(const Ctx &c, Lds &L, int lane)
     });
 }
 
+// Four neighbouring elements of a cached state (element index idx), in the storage type of the cache: fp32, or
+// fp16 / bf16 as caches keep them (Section 5.1: FP16).  A reduced-precision checkpoint is the fp32 running state
+// rounded once to nearest even; the running state itself is never rounded.
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+__device__ __forceinline__ float4 load_state4(const void *base, size_t idx, int state_type)
+{
+    if (state_type == 1) {
+        const f16x4 h = *reinterpret_cast<const f16x4 *>(static_cast<const _Float16 *>(base) + idx);
+        return make_float4((float)h[0], (float)h[1], (float)h[2], (float)h[3]);
+    }
+    if (state_type == 2) {
+        const uint2 u = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(base) + idx);
+        return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                           __uint_as_float(u.y & 0xffff0000u));
+    }
+    return *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + idx);
+}
+__device__ __forceinline__ void store_state4(void *base, size_t idx, float v0, float v1, float v2, float v3, int state_type)
+{
+    if (state_type == 1) {
+        const f16x4 h = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+        *reinterpret_cast<f16x4 *>(static_cast<_Float16 *>(base) + idx) = h;
+    } else if (state_type == 2) {
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(base) + idx) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    } else {
+        *reinterpret_cast<float4 *>(static_cast<float *>(base) + idx) = make_float4(v0, v1, v2, v3);
+    }
+}
+
 // bf16 copy of four neighbouring state values (and, if asked for, of what the rounding took away)
 __device__ __forceinline__ void store_state_copy(Lds &L, int buf, int p, int n0, float v0, float v1, float v2, float v3)
 {
@@ -613,7 +643,7 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane)
             const int n0 = 32 * (NS * SQ + nb) + 8 * a + 4 * q;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (c.init)
-                v = *reinterpret_cast<const float4 *>(c.init + ((size_t)c.h * c.P + c.pbase + p) * kN + n0);
+                v = load_state4(c.init, ((size_t)c.h * c.P + c.pbase + p) * kN + n0, c.state_type);
             S[nb][4 * a + 0] = v.x;
             S[nb][4 * a + 1] = v.y;
             S[nb][4 * a + 2] = v.z;
@@ -680,12 +710,12 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane)
             if (t.ckpt_slot >= 0) {
 #pragma unroll
                 for (int nb = 0; nb < NS; ++nb) {
-                    float *dst = c.state_out + (((size_t)t.ckpt_slot * c.H + c.h) * c.P + c.pbase + p) * kN +
-                                 32 * (NS * SQ + nb) + 4 * q;
+                    const size_t idx = (((size_t)t.ckpt_slot * c.H + c.h) * c.P + c.pbase + p) * kN +
+                                       32 * (NS * SQ + nb) + 4 * q;
 #pragma unroll
                     for (int a = 0; a < 4; ++a)
-                        *reinterpret_cast<float4 *>(dst + 8 * a) =
-                            make_float4(S[nb][4 * a], S[nb][4 * a + 1], S[nb][4 * a + 2], S[nb][4 * a + 3]);
+                        store_state4(c.state_out, idx + 8 * a, S[nb][4 * a], S[nb][4 * a + 1], S[nb][4 * a + 2],
+                                     S[nb][4 * a + 3], c.state_type);
                 }
             }
         }
@@ -761,9 +791,9 @@ __global__ __launch_bounds__(64 * kScoreBlocksPerTile) void ssm_cb_kernel(
 __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A_,
     const bf16_t *__restrict__ Bg, const bf16_t *__restrict__ Cg, const float *__restrict__ D_,
-    bf16_t *__restrict__ y, float *__restrict__ state_out, const float *__restrict__ cb,
-    const float *const *__restrict__ init_ptrs, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P, int G, int p_split,
-    int wg_per_xcd, int n_wg)
+    bf16_t *__restrict__ y, void *__restrict__ state_out, const float *__restrict__ cb,
+    const void *const *__restrict__ init_ptrs, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs,
+    int H, int P, int G, int p_split, int wg_per_xcd, int n_wg, int state_type)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     Lds &L = *reinterpret_cast<Lds *>(lds_raw);
@@ -783,6 +813,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     c.Cg = Cg;
     c.y = y;
     c.state_out = state_out;
+    c.state_type = state_type;
     c.cb = cb;
     c.tiles = tiles;
     c.H = H;
@@ -830,8 +861,12 @@ size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan)
     return plan->tiles.size() * (size_t)plan->shape.ngroups * kScoreBlocksPerTile * kScoreBlockBytes;
 }
 
-hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream)
+// `state_type`: storage of the initial states and of the checkpoints in args.state_out (0 fp32, 1 fp16, 2 bf16).
+hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream,
+                                 int state_type)
 {
+    if (state_type < 0 || state_type > 2)
+        return hipErrorInvalidValue;
     float *cb = static_cast<float *>(workspace);
     static bool attr_set = false;
     const size_t lds = sizeof(Lds);
@@ -853,7 +888,8 @@ hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, voi
     hipLaunchKernelGGL(ssm_scan_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
                        static_cast<const bf16_t *>(args.x), static_cast<const bf16_t *>(args.dt), args.A,
                        static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C), args.D,
-                       static_cast<bf16_t *>(args.y), args.state_out, cb, args.init_ptrs, args.tiles, args.seqs,
-                       args.H, args.P, args.G, args.p_split, per_xcd, n_wg);
+                       static_cast<bf16_t *>(args.y), static_cast<void *>(args.state_out), cb,
+                       reinterpret_cast<const void *const *>(args.init_ptrs), args.tiles, args.seqs, args.H, args.P,
+                       args.G, args.p_split, per_xcd, n_wg, state_type);
     return hipGetLastError();
 }

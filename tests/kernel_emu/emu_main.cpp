@@ -17,7 +17,8 @@
 #ifdef SSM_EMU_CANDIDATE
 // the candidate revision of the matrix-core kernel (tests/kernel_emu/candidate) takes a workspace
 size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
-hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
+hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream,
+                                 int state_type);
 // the candidate roll-forward entry: states advanced in place
 hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs, int state_type,
                                 hipStream_t stream);
@@ -42,6 +43,22 @@ int main(int argc, char **argv)
     if (argc > 5)
         emu::set_drop_barrier(atol(argv[5]));
     const bool advance = argc > 6 && strcmp(argv[6], "advance") == 0;
+    // storage type of cached states for the candidate kernels: argv[7] = f16 | bf16 (default fp32)
+    const int st_type = argc > 7 ? (strcmp(argv[7], "f16") == 0 ? 1 : strcmp(argv[7], "bf16") == 0 ? 2 : 0) : 0;
+    const size_t st_esz = st_type == 0 ? 4 : 2;
+    auto to_state = [&](void *dst, size_t e, float v) {
+        if (st_type == 0)
+            static_cast<float *>(dst)[e] = v;
+        else if (st_type == 1)
+            static_cast<_Float16 *>(dst)[e] = (_Float16)v;
+        else
+            static_cast<bf16_t *>(dst)[e] = f32_to_bf16(v);
+    };
+    auto from_state = [&](const void *src, size_t e) {
+        return st_type == 0   ? static_cast<const float *>(src)[e]
+               : st_type == 1 ? (float)static_cast<const _Float16 *>(src)[e]
+                              : bf16_to_f32(static_cast<const bf16_t *>(src)[e]);
+    };
     FILE *f = fopen(argv[1], "rb");
     if (!f) {
         perror(argv[1]);
@@ -110,20 +127,11 @@ int main(int argc, char **argv)
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
     if (advance) {
 #ifdef SSM_EMU_CANDIDATE
-        const int st_type = argc > 7 ? (strcmp(argv[7], "f16") == 0 ? 1 : strcmp(argv[7], "bf16") == 0 ? 2 : 0) : 0;
-        const size_t st_esz = st_type == 0 ? 4 : 2;
         void **sp = static_cast<void **>(guarded(sizeof(void *) * (batch ? batch : 1), end_aligned));
         for (int b = 0; b < batch; ++b) {
             sp[b] = guarded(nst * st_esz, end_aligned);
-            for (size_t e = 0; e < nst; ++e) {
-                const float v = init[b] ? init[b][e] : 0.f;
-                if (st_type == 0)
-                    static_cast<float *>(sp[b])[e] = v;
-                else if (st_type == 1)
-                    static_cast<_Float16 *>(sp[b])[e] = (_Float16)v;
-                else
-                    static_cast<bf16_t *>(sp[b])[e] = f32_to_bf16(v);
-            }
+            for (size_t e = 0; e < nst; ++e)
+                to_state(sp[b], e, init[b] ? init[b][e] : 0.f);
         }
         if (launch_state_advance(plan, args, sp, st_type, nullptr) != hipSuccess) {
             fprintf(stderr, "launch_state_advance failed\n");
@@ -134,9 +142,7 @@ int main(int argc, char **argv)
         std::vector<float> back(nst);
         for (int b = 0; b < batch; ++b) {
             for (size_t e = 0; e < nst; ++e)
-                back[e] = st_type == 0   ? static_cast<float *>(sp[b])[e]
-                          : st_type == 1 ? (float)static_cast<_Float16 *>(sp[b])[e]
-                                         : bf16_to_f32(static_cast<bf16_t *>(sp[b])[e]);
+                back[e] = from_state(sp[b], e);
             fwrite(back.data(), 4, nst, f);
         }
         fclose(f);
@@ -154,7 +160,26 @@ int main(int argc, char **argv)
             const size_t ws_bytes = scan_mfma_next_workspace_bytes(plan);
             void *ws = guarded(ws_bytes ? ws_bytes : 16, end_aligned);
             memset(ws, 0xFF, ws_bytes);
-            e = launch_scan_mfma_next(plan, args, ws, nullptr);
+            if (st_type != 0) {
+                // cached states in the reduced type: convert the initial ones, give the kernel a checkpoint buffer of
+                // that type, and convert the checkpoints back to fp32 for the output file
+                for (int b = 0; b < batch; ++b)
+                    if (init[b]) {
+                        void *conv = guarded(nst * st_esz, end_aligned);
+                        for (size_t k = 0; k < nst; ++k)
+                            to_state(conv, k, init[b][k]);
+                        init[b] = static_cast<const float *>(conv);
+                    }
+                const size_t nck = (size_t)(n_ckpt ? n_ckpt : 1) * nst;
+                void *st_red = guarded(nck * st_esz, end_aligned);
+                memset(st_red, 0xFF, nck * st_esz);
+                args.state_out = static_cast<float *>(st_red);
+                e = launch_scan_mfma_next(plan, args, ws, nullptr, st_type);
+                for (size_t k = 0; k < (size_t)n_ckpt * nst; ++k)
+                    st[k] = from_state(st_red, k);
+            } else {
+                e = launch_scan_mfma_next(plan, args, ws, nullptr, 0);
+            }
         } else {
             e = launch_scan_valu(plan, args, nullptr);
         }

@@ -156,10 +156,10 @@ def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False,
     if not os.path.exists(pin):
         _write_problem(pin, wl, init)
     cmd = [binary, pin, pout, str(order), align]
-    if drop is not None or advance:
+    if drop is not None or advance or state_type:
         cmd.append(str(-1 if drop is None else drop))
-    if advance:
-        cmd.append("advance")
+    if advance or state_type:
+        cmd.append("advance" if advance else "scan")
         if state_type:
             cmd.append(state_type)
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
@@ -387,6 +387,26 @@ def test_candidate_state_advance_with_reduced_precision_states(emu_candidate_bin
             # and the stored values are values of the type
             assert np.array_equal(torch.from_numpy(st[b].copy()).to(tdt).float().numpy(), st[b])
             k += 1
+
+
+@pytest.mark.parametrize("state_type,ulp", [("f16", 2.0 ** -10), ("bf16", 2.0 ** -7)])
+def test_candidate_scan_with_reduced_precision_states(emu_candidate_binary, tmp_path, state_type, ulp):
+    """The scan candidate with cached states stored as fp16 / bf16: initial states are read in that type, the running
+    state stays fp32, checkpoints are rounded once.  Against the oracle from the same representable initial states:
+    y as usual, checkpoints to one unit in the last place of the type on top of the kernel's own error."""
+    (H, P, N, G, chunk), cfg, kw = CASES["ragged"]
+    shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype="bf16")
+    wl = make_workload(cfg, "cpu", seed=11, shape=shape, **kw)
+    tdt = torch.float16 if state_type == "f16" else torch.bfloat16
+    init = [None if v is None else v.to(tdt).float() for v in wl.init_state]
+    wl.init_state = init
+    y_ref, st_ref = _oracle(wl, init)
+    y, st, _ = _emulate(emu_candidate_binary, wl, init, tmp_path, 1, "end", state_type=state_type)
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(st))
+    assert max(rel_err(y, y_ref)) <= TOL["bf16"]
+    rms = float(np.sqrt(np.mean(st_ref * st_ref)))
+    assert np.all(np.abs(st - st_ref) <= ulp * np.maximum(np.abs(st_ref), rms) + 1e-4 * rms)
+    assert np.array_equal(torch.from_numpy(st.copy()).to(tdt).float().numpy(), st)
 
 
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
