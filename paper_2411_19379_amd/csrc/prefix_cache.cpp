@@ -35,6 +35,7 @@ struct Node {
     int64_t handle = -1;
     int64_t last_access = 0;
     int32_t pins = 0;
+    int32_t holder_index = -1;          // position in the cache's list of state-holding nodes, -1 if none
 };
 
 double prefill_flops(const pc_config_t &c, int64_t L)
@@ -55,6 +56,8 @@ struct pc_cache {
     int64_t kv_tokens = 0;
     int64_t n_states = 0;
     int64_t n_nodes = 0;
+    std::vector<Node *> holders;    // every node that holds a state, in no particular order
+    std::vector<double> scratch_ts, scratch_fe, scratch_s;
     std::vector<int64_t> released;  // of the last pc_finish: evicted, then rejected
     int32_t n_evicted_last = 0;
 
@@ -152,6 +155,26 @@ struct pc_cache {
         }
     }
 
+    void give_state(Node *n, int64_t handle)
+    {
+        n->has_state = true;
+        n->handle = handle;
+        n->holder_index = (int32_t)holders.size();
+        holders.push_back(n);
+        ++n_states;
+    }
+
+    void take_state(Node *n)
+    {
+        Node *last = holders.back();
+        holders[n->holder_index] = last;
+        last->holder_index = n->holder_index;
+        holders.pop_back();
+        n->holder_index = -1;
+        n->has_state = false;
+        --n_states;
+    }
+
     // A node without state and with exactly one child is not a node: join its edge to the child's.
     void merge_into_child(Node *n)
     {
@@ -172,8 +195,7 @@ struct pc_cache {
 
     void evict(Node *n)
     {
-        n->has_state = false;
-        --n_states;
+        take_state(n);
         if (n->children.empty()) {
             // leaf: its KVs go with it
             Node *p = n->parent;
@@ -188,15 +210,6 @@ struct pc_cache {
         }
     }
 
-    void collect(Node *n, std::vector<Node *> *holders)
-    {
-        for (auto &kv : n->children) {
-            if (kv.second->has_state)
-                holders->push_back(kv.second);
-            collect(kv.second, holders);
-        }
-    }
-
     double flop_efficiency(const Node *n) const
     {
         // FLOPs saved relative to the parent over the bytes of this node's own KVs and state (Eq. 1)
@@ -206,23 +219,34 @@ struct pc_cache {
         return saved / (double)mem;
     }
 
-    // S(n) of Eq. 2 for every state-holding node, both terms min-max normalised over those nodes
-    void scores(const std::vector<Node *> &holders, std::vector<double> *s) const
+    // S(n) of Eq. 2 for every state-holding node (same order as `holders`), both terms min-max normalised over
+    // those nodes
+    void scores(std::vector<double> *s)
     {
         const size_t k = holders.size();
-        s->assign(k, 0.0);
+        s->resize(k);
         if (k == 0)
             return;
-        std::vector<double> ts(k), fe(k);
+        scratch_ts.resize(k);
+        scratch_fe.resize(k);
+        double tlo = 0, thi = 0, flo = 0, fhi = 0;
         for (size_t i = 0; i < k; ++i) {
-            ts[i] = (double)holders[i]->last_access;
-            fe[i] = flop_efficiency(holders[i]);
+            const double t = (double)holders[i]->last_access, f = flop_efficiency(holders[i]);
+            scratch_ts[i] = t;
+            scratch_fe[i] = f;
+            if (i == 0) {
+                tlo = thi = t;
+                flo = fhi = f;
+            } else {
+                tlo = t < tlo ? t : tlo;
+                thi = t > thi ? t : thi;
+                flo = f < flo ? f : flo;
+                fhi = f > fhi ? f : fhi;
+            }
         }
-        const double tlo = *std::min_element(ts.begin(), ts.end()), thi = *std::max_element(ts.begin(), ts.end());
-        const double flo = *std::min_element(fe.begin(), fe.end()), fhi = *std::max_element(fe.begin(), fe.end());
         for (size_t i = 0; i < k; ++i) {
-            const double r = thi > tlo ? (ts[i] - tlo) / (thi - tlo) : 0.0;
-            const double f = fhi > flo ? (fe[i] - flo) / (fhi - flo) : 0.0;
+            const double r = thi > tlo ? (scratch_ts[i] - tlo) / (thi - tlo) : 0.0;
+            const double f = fhi > flo ? (scratch_fe[i] - flo) / (fhi - flo) : 0.0;
             (*s)[i] = r + cfg.alpha * f;
         }
     }
@@ -254,19 +278,16 @@ struct pc_cache {
 
     Node *pick_victim(Node *own0, Node *own1)
     {
-        std::vector<Node *> holders;
-        collect(&root, &holders);
-        std::vector<double> s;
-        scores(holders, &s);
+        scores(&scratch_s);
         Node *best = nullptr;
         double best_s = 0.0;
         for (size_t i = 0; i < holders.size(); ++i) {
             Node *n = holders[i];
             if (n == own0 || n == own1 || n->pins > 0 || n->children.size() > 1)
                 continue;
-            if (!best || goes_first(s[i], n, best_s, best)) {
+            if (!best || goes_first(scratch_s[i], n, best_s, best)) {
                 best = n;
-                best_s = s[i];
+                best_s = scratch_s[i];
             }
         }
         return best;
@@ -282,6 +303,10 @@ struct pc_cache {
         n->handle = src->handle;
         n->last_access = src->last_access;
         n->pins = src->pins;
+        if (n->has_state) {
+            n->holder_index = (int32_t)holders.size();
+            holders.push_back(n);
+        }
         for (auto &kv : src->children)
             n->children[kv.first] = clone_subtree(kv.second, n);
         return n;
@@ -426,9 +451,7 @@ extern "C" int pc_finish(pc_cache_t *cache, const int32_t *tokens, int32_t m, in
         if (n->has_state) {
             rejected.push_back(handles[i]);  // a state is already cached for this prefix: keep it
         } else {
-            n->has_state = true;
-            n->handle = handles[i];
-            ++cache->n_states;
+            cache->give_state(n, handles[i]);
         }
         n->last_access = now;
         own[i] = n;
@@ -496,14 +519,9 @@ extern "C" int pc_node_score(const pc_cache_t *cache, const int32_t *tokens, int
     Node *n = c->walk(tokens, depth, &matched, &child, &in_edge);
     if (matched != depth || in_edge != 0 || !n->has_state)
         return fail(PC_ERR_BAD_REQUEST, "no state is cached for this prefix");
-    std::vector<Node *> holders;
-    c->collect(&c->root, &holders);
     std::vector<double> s;
-    c->scores(holders, &s);
-    for (size_t i = 0; i < holders.size(); ++i)
-        if (holders[i] == n) {
-            *score = s[i];
-            return PC_OK;
-        }
-    return fail(PC_ERR_BAD_REQUEST, "no state is cached for this prefix");
+    c->scores(&s);
+    *score = s[n->holder_index];
+    return PC_OK;
 }
+
