@@ -60,6 +60,8 @@ void *g_arg = nullptr;
 int g_order_mode = 0;  // 0 forward, 1 reverse, >=2 shuffle with this seed
 long g_drop_barrier = -1;  // self-test of the checker: the barrier with this ordinal does not wait
 long g_switches = 0;
+bool (*g_block_filter)(int, unsigned) = nullptr;  // optional: which blocks of which launch to run
+int g_launch_index = 0;
 
 [[noreturn]] void die(const char *msg, int a = 0, int b = 0)
 {
@@ -332,6 +334,8 @@ Idx &thread_idx() { return cur->tid; }
 Idx &block_idx() { return g_block; }
 unsigned char *lds_base() { return g_lds; }
 void set_order_mode(int m) { g_order_mode = m; }
+// Run only the blocks for which filter(launch ordinal, linear block index) is true (for spot checks of large grids).
+void set_block_filter(bool (*filter)(int, unsigned)) { g_block_filter = filter; }
 long switches() { return g_switches; }
 
 void set_drop_barrier(long n) { g_drop_barrier = n; }
@@ -428,7 +432,10 @@ void launch_impl(dim3 grid, dim3 block, size_t lds_bytes, void (*fn)(void *), vo
     mprotect(m, page, PROT_NONE);
     mprotect(m + page + span, page, PROT_NONE);
     g_lds = m + page + span - ((lds_bytes + 15) / 16 * 16);
+    const int launch = g_launch_index++;
     for (unsigned b = 0; b < grid.x * grid.y * grid.z; ++b) {
+        if (g_block_filter && !g_block_filter(launch, b))
+            continue;
         g_block = Idx{b % grid.x, (b / grid.x) % grid.y, b / (grid.x * grid.y)};
         memset(g_lds, 0xFF, (lds_bytes + 15) / 16 * 16);
         run_block(block);

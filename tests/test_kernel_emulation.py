@@ -409,6 +409,30 @@ def test_candidate_scan_with_reduced_precision_states(emu_candidate_binary, tmp_
     assert np.array_equal(torch.from_numpy(st.copy()).to(tdt).float().numpy(), st)
 
 
+@pytest.mark.parametrize("which", ["shipped", "candidate"])
+def test_full_size_spot_check(tmp_path_factory, which):
+    """The 7B-shaped 32K-token configuration (H=128, P=64, N=128, G=8, one checkpoint at the end) on the emulator:
+    only the first two and the last workgroup run, on guarded buffers of the full size, and are compared with a
+    plain fp64 recurrence inside the driver.  Token offsets, group indexing and the workgroup renumbering are the
+    real ones."""
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ with bf16 vector support found")
+    d = str(tmp_path_factory.mktemp("kernel_emu_big_" + which))
+    src = os.path.join(CSRC, "scan_mfma.hip") if which == "shipped" else os.path.join(EMU, "candidate", "scan_mfma_next.hip")
+    _convert(src, os.path.join(d, "scan_mfma.cpp"))
+    flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
+             "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    if which == "candidate":
+        flags.append("-DSSM_EMU_CANDIDATE")
+    out = os.path.join(d, "emu_big")
+    r = subprocess.run([CLANG, *flags, os.path.join(d, "scan_mfma.cpp"), os.path.join(CSRC, "plan.cpp"),
+                        os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_big.cpp"), "-o", out],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    r = subprocess.run([out, "32768", "32768"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and "BIG CHECK OK" in r.stdout, r.stdout[-1500:] + r.stderr[-500:]
+
+
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
     """Self-test of the race check on the bf16 kernel: with the barrier of one
     pipeline step made not to wait, forward and reverse wave order disagree."""
