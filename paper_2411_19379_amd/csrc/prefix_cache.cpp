@@ -361,8 +361,13 @@ extern "C" int pc_clone(const pc_cache_t *cache, pc_cache_t **out)
     c->kv_tokens = cache->kv_tokens;
     c->n_states = cache->n_states;
     c->n_nodes = cache->n_nodes;
-    for (auto &kv : cache->root.children)
-        c->root.children[kv.first] = c->clone_subtree(kv.second, &c->root);
+    try {
+        for (auto &kv : cache->root.children)
+            c->root.children[kv.first] = c->clone_subtree(kv.second, &c->root);
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return fail(PC_ERR_INVALID_ARG, "out of host memory");
+    }
     *out = c;
     return PC_OK;
 }
@@ -408,9 +413,26 @@ extern "C" int pc_begin(pc_cache_t *cache, const int32_t *tokens, int32_t n, int
     return PC_OK;
 }
 
+static int finish_impl(pc_cache_t *cache, const int32_t *tokens, int32_t m, int32_t hit_len, int32_t checkpoint_pos,
+                       int64_t branch_handle, int64_t final_handle, int64_t now, int32_t *n_evicted,
+                       int32_t *n_rejected);
+
+// No exception crosses the C boundary: running out of host memory is reported as an error code.
 extern "C" int pc_finish(pc_cache_t *cache, const int32_t *tokens, int32_t m, int32_t hit_len, int32_t checkpoint_pos,
                          int64_t branch_handle, int64_t final_handle, int64_t now, int32_t *n_evicted,
                          int32_t *n_rejected)
+{
+    try {
+        return finish_impl(cache, tokens, m, hit_len, checkpoint_pos, branch_handle, final_handle, now, n_evicted,
+                           n_rejected);
+    } catch (const std::bad_alloc &) {
+        return fail(PC_ERR_INVALID_ARG, "out of host memory");
+    }
+}
+
+static int finish_impl(pc_cache_t *cache, const int32_t *tokens, int32_t m, int32_t hit_len, int32_t checkpoint_pos,
+                       int64_t branch_handle, int64_t final_handle, int64_t now, int32_t *n_evicted,
+                       int32_t *n_rejected)
 {
     if (!cache || !tokens || m <= 0 || !n_evicted || !n_rejected)
         return fail(PC_ERR_INVALID_ARG, "cache, tokens or a count pointer is NULL, or the sequence is empty");
