@@ -78,6 +78,9 @@ constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_XS_SPLIT
 #define SSM_XS_SPLIT 1  // 1: the decay-weighted x enters the state update as a bf16 pair (value, rounding remainder)
 #endif
+#ifndef SSM_WAVE_PRIO
+#define SSM_WAVE_PRIO 0  // 1: the output and state waves (the long dependent chains) run at a raised wave priority
+#endif
 #ifndef SSM_SS_SPLIT
 #define SSM_SS_SPLIT 0  // 1: the copy of S used for S.C is a bf16 pair too (y after a resume from a large cached state)
 #endif
@@ -551,6 +554,9 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
     const int g4 = lane >> 4;
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
     const int tr_row = 4 * (g4 >> 1) + ((lane & 15) >> 2);
+#if SSM_WAVE_PRIO
+    __builtin_amdgcn_s_setprio(2);
+#endif
     SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         SSM_TRACE(2);
@@ -656,6 +662,9 @@ __device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane)
     const int g4 = lane >> 4;
     const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
+#if SSM_WAVE_PRIO
+    __builtin_amdgcn_s_setprio(1);
+#endif
     SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         SSM_TRACE(2);

@@ -80,6 +80,7 @@ template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&b
 #define __shfl(v, l, w) __uint_as_float((uint32_t)emu::shfl((int)__float_as_uint(v), (l), __LINE__))
 #define __builtin_amdgcn_exp2f(x) exp2f(x)
 #define __builtin_amdgcn_rcpf(x) (1.0f / (x))
+#define __builtin_amdgcn_s_setprio(x) ((void)0)
 #define __builtin_amdgcn_logf(x) log2f(x)
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \
