@@ -78,6 +78,9 @@ constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_XS_SPLIT
 #define SSM_XS_SPLIT 1  // 1: the decay-weighted x enters the state update as a bf16 pair (value, rounding remainder)
 #endif
+#ifndef SSM_DEFER_Y
+#define SSM_DEFER_Y 0  // 1: an output wave stores the y of a tile at the start of its next step, under the LDS reads
+#endif
 #ifndef SSM_WAVE_PRIO
 #define SSM_WAVE_PRIO 0  // 1: the output and state waves (the long dependent chains) run at a raised wave priority
 #endif
@@ -557,6 +560,21 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
 #if SSM_WAVE_PRIO
     __builtin_amdgcn_s_setprio(2);
 #endif
+    bf16_t(*ys)[LDY] = L.Ys[IH];
+    // rows of this wave's staging tile to device memory: 16 bytes per lane, four lanes per 64-byte row of y
+    auto flush_y = [&](const SsmTile &t) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int tok = (lane >> 2) + 16 * m;
+            const uint4 o = *reinterpret_cast<const uint4 *>(&ys[tok][8 * (lane & 3)]);
+            if (32 * IH + tok < t.len)
+                *reinterpret_cast<uint4 *>(c.y + (((size_t)t.tok0 + 32 * IH + tok) * c.H + c.h) * c.P + c.pbase +
+                                           8 * (lane & 3)) = o;
+        }
+    };
+#if SSM_DEFER_Y
+    SsmTile t_prev = tile_at(c, 0);
+#endif
     SSM_TRACE_DECL
     pipe_loop(c.n_tiles, [&](int s, auto U) {
         SSM_TRACE(2);
@@ -593,6 +611,12 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
                 m1 = L.M10[s & 1][lane][1];
             }
             const float ei = L.tab[b].ei[32 * IH + i];
+#if SSM_DEFER_Y
+            // y of the previous tile: staged before the last barrier, stored now, under the reads just issued
+            if (s > 0)
+                flush_y(t_prev);
+            t_prev = t;
+#endif
             // S_s C_i with the state as it was before this tile
             f32x16 Y = zero16();
 #pragma unroll
@@ -616,23 +640,20 @@ __device__ __forceinline__ void role_output(const Ctx &c, Lds &L, int lane)
             // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of
             // token i.  Through this wave's own LDS tile to token-major rows, then
             // 16 bytes per lane with four lanes per 64-byte row of y.
-            bf16_t(*ys)[LDY] = L.Ys[IH];
 #pragma unroll
             for (int a = 0; a < 4; ++a)
                 *reinterpret_cast<uint2 *>(&ys[i][8 * a + 4 * q]) =
                     make_uint2(pack2(Y[4 * a], Y[4 * a + 1]), pack2(Y[4 * a + 2], Y[4 * a + 3]));
+#if !SSM_DEFER_Y
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // same wave: LDS executes in order
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const int tok = (lane >> 2) + 16 * m;
-                const uint4 o = *reinterpret_cast<const uint4 *>(&ys[tok][8 * (lane & 3)]);
-                if (32 * IH + tok < t.len)
-                    *reinterpret_cast<uint4 *>(c.y + (((size_t)t.tok0 + 32 * IH + tok) * c.H + c.h) * c.P + c.pbase +
-                                               8 * (lane & 3)) = o;
-            }
+            flush_y(t);
+#endif
         }
         SSM_TRACE(1);
     });
+#if SSM_DEFER_Y
+    flush_y(t_prev);  // the last tile; the loop's final barrier has ordered its staging writes
+#endif
 }
 
 // ---------------------------------------------------------------- state update of tile k, NS x 32 state indices

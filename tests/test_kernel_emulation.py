@@ -237,13 +237,15 @@ def test_candidate_kernel_matches_oracle_in_any_wave_order(emu_candidate_binary,
 
 @pytest.fixture(scope="session")
 def emu_candidate_split_binary(tmp_path_factory):
-    """The candidate with the bf16 copy of S carried as a pair as well (off by default)."""
+    """The candidate with its optional paths on: the bf16 copy of S carried as a pair as well, y stored one step
+    late by the output waves, raised wave priorities (a no-op here)."""
     return _build(tmp_path_factory, "kernel_emu_candidate_split",
-                  os.path.join(EMU, "candidate", "scan_mfma_next.hip"), ["-DSSM_EMU_CANDIDATE", "-DSSM_SS_SPLIT=1"],
+                  os.path.join(EMU, "candidate", "scan_mfma_next.hip"),
+                  ["-DSSM_EMU_CANDIDATE", "-DSSM_SS_SPLIT=1", "-DSSM_DEFER_Y=1", "-DSSM_WAVE_PRIO=1"],
                   [os.path.join(EMU, "candidate", "state_advance.hip")])
 
 
-@pytest.mark.parametrize("case", ["ragged", "p32_groups", "empty_seq"])
+@pytest.mark.parametrize("case", ["ragged", "p32_groups", "empty_seq", "tiny", "long"])
 def test_candidate_with_state_copy_split(emu_candidate_split_binary, tmp_path, case):
     """With both pairs on, y after a resume from an O(1) cached state stays within half the bf16 budget."""
     _check_case(emu_candidate_split_binary, tmp_path, "bf16", case, state_tol=1e-4, y_tol=1e-2)
