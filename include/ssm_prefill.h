@@ -48,6 +48,12 @@ typedef enum {
 
 typedef enum { SSM_DT_F32 = 0, SSM_DT_BF16 = 1 } ssm_dtype_t; /* type of x, dt, B, C, y */
 
+/* Storage type of cached states: the initial states a call reads and the checkpoints it writes.  The paper's cache
+ * holds FP16 states (Section 5.1; Appendix A.1 counts 2 bytes per state element); fp32 keeps every bit of the
+ * running state.  The running state inside a call is fp32 whatever the storage type; a reduced-precision
+ * checkpoint is that fp32 state rounded once, to nearest even. */
+typedef enum { SSM_ST_F32 = 0, SSM_ST_F16 = 1, SSM_ST_BF16 = 2 } ssm_state_dtype_t;
+
 typedef struct {
     int32_t nheads;    /* H */
     int32_t headdim;   /* P */
@@ -57,6 +63,7 @@ typedef struct {
                           knob that changes rounding order only, never which state is
                           returned.  16 <= Q <= 256, multiple of 16. */
     int32_t io_dtype;  /* ssm_dtype_t */
+    int32_t state_dtype; /* ssm_state_dtype_t */
 } ssm_shape_t;
 
 typedef struct ssm_plan ssm_plan_t; /* opaque; owned by the library */
@@ -96,24 +103,37 @@ int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
                     const int32_t *ckpt_pos_host,
                     ssm_plan_t **out);
 
-/* Copy the plan's summary into *info. */
+/* Copy the plan's summary into *info: what the planner of Section 4.1's chunked prefill decided for this batch
+ * (how many tiles, which kernel family, how many checkpoint slots).  SSM_ERR_INVALID_ARG if either pointer is NULL. */
 int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info);
 
 /* Read tile i (0 <= i < n_tiles) of the plan: first packed token, length,
- * owning sequence, and the checkpoint slot filled at its end (-1: none). */
+ * owning sequence, and the checkpoint slot filled at its end (-1: none).
+ * This is the chunking of Section 4.1 made visible: a caller can check that
+ * every requested position is a tile end.  Any output pointer may be NULL;
+ * SSM_ERR_INVALID_ARG if the plan is NULL or i is out of range. */
 int ssm_plan_tile(const ssm_plan_t *plan, int32_t i, int32_t *tok0, int32_t *len,
                   int32_t *seq, int32_t *ckpt_slot);
 
-/* Bytes of device workspace ssm_prefill needs for this plan (may be 0). The
- * caller allocates it, 256-byte aligned, and may reuse it between calls. */
+/* Bytes of device workspace ssm_prefill needs for this plan (may be 0): the
+ * per-(tile, group) operands that the heads of a group share in the chunked
+ * scan of Section 4.1.  The caller allocates it, 256-byte aligned, owns it,
+ * and may reuse it between calls that do not overlap; its contents mean
+ * nothing between calls. */
 int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes);
 
 /*
  * Enqueue the scan of one SSM layer on `hip_stream` (a hipStream_t, NULL =
- * the default stream).  Never synchronises the stream.  The first call with a
- * plan uploads the plan's tile table (one small device allocation owned by
- * the plan and a blocking copy); later calls only enqueue.  A plan must not
- * be used by calls that overlap on different streams.
+ * the default stream): the chunked prefill of Section 4.1 with cached-state
+ * resume (Section 2.2) and exact-position checkpoints.
+ *
+ * Synchronisation: the first call with a plan on a GPU makes three small
+ * device allocations owned by the plan and waits once for the upload of the
+ * plan's tables on `hip_stream`; every later call with that plan only
+ * enqueues and never synchronises.  The plan itself is not modified (the
+ * device tables are a cache behind it).  Calls that share a plan must be
+ * ordered against each other (one stream, or events): they share the plan's
+ * buffer of state pointers.
  *
  *   x      [T,H,P]  io_dtype  device  read only
  *   dt     [T,H]    io_dtype  device  read only; final step sizes, positive
@@ -121,33 +141,89 @@ int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes);
  *   A      [H]      fp32      device  read only; negative decay rates
  *   B, C   [T,G,N]  io_dtype  device  read only
  *   D      [H]      fp32      device  read only; skip weight per head
- *   init_state_ptrs [batch]   HOST array of DEVICE pointers to fp32 [H,P,N];
- *                             the array or any entry may be NULL (zero state).
- *                             The states are read only: they are live cache
- *                             entries.  The array is copied before return.
+ *   init_state_ptrs [batch]   HOST array of DEVICE pointers to [H,P,N] in the
+ *                             plan's state_dtype; the array or any entry may
+ *                             be NULL (zero state).  The states are read only:
+ *                             they are live cache entries.  The array has been
+ *                             copied when the call returns.
  *   y_out  [T,H,P]  io_dtype  device  written
- *   state_out [n_ckpt,H,P,N] fp32 device written; slot order = sequence
- *                             major, then ascending position (CSR order); a
- *                             slot may be passed back as an initial state of
- *                             a later call unchanged.  May be NULL if n_ckpt
- *                             is 0.
- *   workspace       device, >= ssm_plan_workspace_bytes; may be NULL if 0
+ *   state_out [n_ckpt,H,P,N]  state_dtype, device, written; slot order =
+ *                             sequence major, then ascending position (CSR
+ *                             order); a slot may be passed back as an initial
+ *                             state of a later call unchanged.  May be NULL if
+ *                             n_ckpt is 0.
+ *   workspace       device, >= ssm_plan_workspace_bytes, 256-byte aligned;
+ *                   may be NULL if that is 0
  *
  * Device pointers must be 16-byte aligned.  T == 0 succeeds and enqueues
- * nothing.
+ * nothing.  Errors: SSM_ERR_INVALID_ARG (a required pointer is NULL),
+ * SSM_ERR_MISALIGNED, SSM_ERR_WORKSPACE_TOO_SMALL, SSM_ERR_HIP.
  */
-int ssm_prefill(ssm_plan_t *plan,
+int ssm_prefill(const ssm_plan_t *plan,
                 const void *x, const void *dt, const float *A,
                 const void *B, const void *C, const float *D,
-                const float *const *init_state_ptrs,
-                void *y_out, float *state_out,
+                const void *const *init_state_ptrs,
+                void *y_out, void *state_out,
                 void *workspace, size_t workspace_bytes,
                 void *hip_stream);
 
-/* Release the plan and its device table.  NULL is accepted. */
+/*
+ * Roll cached states forward (Section 4.1, "Obtaining states during
+ * prefill": a kernel that rolls a checkpointed state forward by a few tokens
+ * to reach an exact position); with one token per sequence it is the decode
+ * step.  Every sequence of the plan brings its own [H,P,N] state in the
+ * plan's state_dtype, which is advanced IN PLACE by the sequence's tokens with
+ * the token recurrence in fp32 and rounded once on the way back.
+ *
+ *   state_ptrs [batch]  HOST array of DEVICE pointers; a NULL entry leaves
+ *                       that sequence alone (its y rows are not written)
+ *   y_out      [T,H,P]  io_dtype, device, or NULL if y is not wanted
+ *
+ * Checkpoints of the plan are ignored.  d_state must be a power of two in
+ * 4..256, else SSM_ERR_UNSUPPORTED_SHAPE.  Enqueues on hip_stream; first use
+ * of a plan as for ssm_prefill.
+ */
+int ssm_state_advance(const ssm_plan_t *plan,
+                      const void *x, const void *dt, const float *A,
+                      const void *B, const void *C, const float *D,
+                      void *const *state_ptrs, void *y_out, void *hip_stream);
+
+/*
+ * Causal depthwise convolution in front of the scan, with cached-state resume
+ * and state checkpoints (the conv_1d state of Appendix A.1: in_channels x
+ * conv_kernel values per layer).  For channel c, kernel width K =
+ * kernel_width (1..4) and the sequence-local token t:
+ *
+ *     out[t,c] = act(bias[c] + sum_{j<K} weight[c,j] * z[t-K+1+j, c])
+ *
+ * where z continues the input to the left by the cached prefix's last inputs
+ * (zeros without one); weight[c,K-1] multiplies the current token; activation
+ * 0 is the identity, 1 is SiLU.
+ *
+ *   in, out    [T,channels]   io_dtype of the plan, device
+ *   weight     [channels,K]   fp32, device;  bias [channels] fp32 or NULL
+ *   init_state_ptrs           NULL, or HOST array [batch] of DEVICE pointers
+ *                             (NULL entry: zeros) to [channels,K] in io_dtype:
+ *                             the last K inputs of the cached prefix, oldest
+ *                             first
+ *   state_out  [n_ckpt,channels,K] io_dtype: one state per checkpoint of the
+ *                             plan, in the plan's slot order; a slot can be
+ *                             passed back as an initial state unchanged
+ *
+ * Only the plan's sequences, checkpoints and io_dtype are used, not its head
+ * shape.  channels must make a row a multiple of 16 bytes.
+ */
+int ssm_conv1d_prefill(const ssm_plan_t *plan, int32_t channels, int32_t kernel_width,
+                       const void *in, const float *weight, const float *bias,
+                       const void *const *init_state_ptrs, void *out, void *state_out,
+                       int32_t activation, void *hip_stream);
+
+/* Release the plan and the device tables it made on first use (Section 4.1's
+ * plan lives exactly as long as the batch it describes).  NULL is accepted. */
 void ssm_plan_destroy(ssm_plan_t *plan);
 
-/* Message of the last error on the calling thread ("" if none). The pointer
+/* Message of the last error on the calling thread ("" if none).  Every entry
+ * point above sets it when it returns a negative ssm_status_t.  The pointer
  * stays valid until the next failing call on this thread. */
 const char *ssm_last_error(void);
 

@@ -4,8 +4,12 @@ package is the thin ctypes binding over its C ABI (include/ssm_prefill.h)."""
 from .binding import (  # noqa: F401
     SSM_DT_BF16,
     SSM_DT_F32,
+    SSM_ERR_UNSUPPORTED_SHAPE,
     SSM_PATH_MFMA_BF16,
     SSM_PATH_VALU_F32,
+    SSM_ST_BF16,
+    SSM_ST_F16,
+    SSM_ST_F32,
     Plan,
     SsmError,
     SsmShape,
@@ -18,5 +22,7 @@ from .binding import (  # noqa: F401
     ssm_plan_info,
     ssm_plan_tile,
     ssm_plan_workspace_bytes,
+    ssm_conv1d_prefill,
     ssm_prefill,
+    ssm_state_advance,
 )

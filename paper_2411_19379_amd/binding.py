@@ -16,7 +16,11 @@ _LIB_PATH = os.path.join(_PKG, "libssm_prefill.so")
 _lib = None
 
 SSM_DT_F32, SSM_DT_BF16 = 0, 1
+SSM_ST_F32, SSM_ST_F16, SSM_ST_BF16 = 0, 1, 2
+_STATE_DTYPES = {"f32": SSM_ST_F32, "f16": SSM_ST_F16, "bf16": SSM_ST_BF16}
 SSM_PATH_VALU_F32, SSM_PATH_MFMA_BF16 = 0, 1
+
+SSM_ERR_UNSUPPORTED_SHAPE = -4
 
 _STATUS = {0: "SSM_OK", -1: "SSM_ERR_INVALID_ARG", -2: "SSM_ERR_BAD_CU_SEQLENS",
            -3: "SSM_ERR_BAD_CHECKPOINT", -4: "SSM_ERR_UNSUPPORTED_SHAPE",
@@ -33,7 +37,8 @@ class SsmError(RuntimeError):
 class SsmShape(ctypes.Structure):
     _fields_ = [("nheads", ctypes.c_int32), ("headdim", ctypes.c_int32),
                 ("d_state", ctypes.c_int32), ("ngroups", ctypes.c_int32),
-                ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32)]
+                ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("state_dtype", ctypes.c_int32)]
 
 
 class SsmPlanInfo(ctypes.Structure):
@@ -75,6 +80,11 @@ def load_library():
     lib.ssm_prefill.restype = ctypes.c_int
     lib.ssm_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp,
                                 ctypes.c_size_t, vp]
+    lib.ssm_state_advance.restype = ctypes.c_int
+    lib.ssm_state_advance.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp]
+    lib.ssm_conv1d_prefill.restype = ctypes.c_int
+    lib.ssm_conv1d_prefill.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.POINTER(vp), vp, vp,
+                                       ctypes.c_int32, vp]
     lib.ssm_plan_destroy.restype = None
     lib.ssm_plan_destroy.argtypes = [vp]
     lib.ssm_last_error.restype = ctypes.c_char_p
@@ -136,27 +146,52 @@ def ssm_plan_destroy(plan: Optional[int]):
         load_library().ssm_plan_destroy(plan)
 
 
+def _ptr_array(plan: int, ptrs):
+    """Host array of device addresses, one per sequence of the plan (the C side reads exactly `batch` entries)."""
+    if ptrs is None:
+        return None
+    batch = ssm_plan_info(plan).batch
+    if len(ptrs) != batch:
+        raise ValueError(f"expected one state pointer per sequence ({batch}), got {len(ptrs)}")
+    arr = (ctypes.c_void_p * max(batch, 1))()
+    for i, p in enumerate(ptrs):
+        arr[i] = p if p else None
+    return arr
+
+
 def ssm_prefill(plan: int, x: int, dt: int, A: int, B: int, C: int, D: int,
                 init_state_ptrs: Optional[Sequence[Optional[int]]], y_out: int, state_out: Optional[int],
                 workspace: Optional[int], workspace_bytes: int, hip_stream: Optional[int]):
     """Raw call: every tensor argument is a device address (int)."""
-    lib = load_library()
-    arr = None
-    if init_state_ptrs is not None:
-        arr = (ctypes.c_void_p * max(len(init_state_ptrs), 1))()
-        for i, p in enumerate(init_state_ptrs):
-            arr[i] = p if p else None
-    _check(lib.ssm_prefill(plan, x, dt, A, B, C, D, arr, y_out, state_out, workspace,
-                           workspace_bytes, hip_stream))
+    _check(load_library().ssm_prefill(plan, x, dt, A, B, C, D, _ptr_array(plan, init_state_ptrs), y_out, state_out,
+                                      workspace, workspace_bytes, hip_stream))
+
+
+def ssm_state_advance(plan: int, x: int, dt: int, A: int, B: int, C: int, D: int,
+                      state_ptrs: Sequence[Optional[int]], y_out: Optional[int], hip_stream: Optional[int]):
+    """Raw call: advance every sequence's [H,P,N] state (in the plan's state dtype) in place."""
+    _check(load_library().ssm_state_advance(plan, x, dt, A, B, C, D, _ptr_array(plan, state_ptrs), y_out,
+                                            hip_stream))
+
+
+def ssm_conv1d_prefill(plan: int, channels: int, kernel_width: int, xin: int, weight: int, bias: Optional[int],
+                       init_state_ptrs: Optional[Sequence[Optional[int]]], out: int, state_out: Optional[int],
+                       activation: int, hip_stream: Optional[int]):
+    """Raw call of the causal convolution with cached-state resume; tensor arguments are device addresses."""
+    _check(load_library().ssm_conv1d_prefill(plan, channels, kernel_width, xin, weight, bias,
+                                             _ptr_array(plan, init_state_ptrs), out, state_out, activation,
+                                             hip_stream))
 
 
 class Plan:
     """Owns an ssm_plan_t for one packed batch."""
 
     def __init__(self, nheads: int, headdim: int, d_state: int, ngroups: int, chunk: int,
-                 io_dtype: str, cu_seqlens, ckpt_pos: Optional[List[List[int]]] = None):
+                 io_dtype: str, cu_seqlens, ckpt_pos: Optional[List[List[int]]] = None,
+                 state_dtype: str = "f32"):
         self.shape = SsmShape(nheads, headdim, d_state, ngroups, chunk,
-                              SSM_DT_F32 if io_dtype == "f32" else SSM_DT_BF16)
+                              SSM_DT_F32 if io_dtype == "f32" else SSM_DT_BF16, _STATE_DTYPES[state_dtype])
+        self._workspace = {}
         cu = _i32(cu_seqlens)
         batch = cu.shape[0] - 1
         cu_ck = flat = None
@@ -172,10 +207,21 @@ class Plan:
     def tiles(self):
         return [ssm_plan_tile(self.handle, i) for i in range(self.info.n_tiles)]
 
+    def workspace(self, device):
+        """The plan's device workspace as a torch tensor (allocated once per device, reused by every call)."""
+        import torch
+
+        key = str(device)
+        if key not in self._workspace:
+            n = ssm_plan_workspace_bytes(self.handle)
+            self._workspace[key] = torch.empty((n,), dtype=torch.uint8, device=device) if n else None
+        return self._workspace[key]
+
     def close(self):
         if getattr(self, "handle", None):
             ssm_plan_destroy(self.handle)
             self.handle = None
+            self._workspace = {}
 
     def __del__(self):
         try:
@@ -184,15 +230,23 @@ class Plan:
             pass
 
 
+def _state_torch_dtype(shape):
+    import torch
+
+    return {SSM_ST_F32: torch.float32, SSM_ST_F16: torch.float16, SSM_ST_BF16: torch.bfloat16}[shape.state_dtype]
+
+
 def prefill(plan: Plan, x, dt, A, B, C, D, init_states=None, y_out=None, state_out=None,
-            stream=None):
+            stream=None, entry=None):
     """Scan one layer on torch CUDA tensors.  Allocates y/state_out with torch
     if not given; returns (y, state_out).  `init_states` is None or a list
-    with one fp32 [H,P,N] CUDA tensor or None per sequence."""
+    with one [H,P,N] CUDA tensor (in the plan's state dtype) or None per
+    sequence.  `entry` selects the raw entry point (default ssm_prefill)."""
     import torch
 
     s = plan.shape
     io = torch.float32 if s.io_dtype == SSM_DT_F32 else torch.bfloat16
+    sdt = _state_torch_dtype(s)
     T = int(plan.info.total_tokens)
     for name, t, shp, dty in (("x", x, (T, s.nheads, s.headdim), io), ("dt", dt, (T, s.nheads), io),
                               ("A", A, (s.nheads,), torch.float32),
@@ -207,24 +261,25 @@ def prefill(plan: Plan, x, dt, A, B, C, D, init_states=None, y_out=None, state_o
         y_out = torch.empty((T, s.nheads, s.headdim), dtype=io, device=dev)
     n_ckpt = int(plan.info.n_ckpt)
     if state_out is None and n_ckpt:
-        state_out = torch.empty((n_ckpt, s.nheads, s.headdim, s.d_state), dtype=torch.float32, device=dev)
+        state_out = torch.empty((n_ckpt, s.nheads, s.headdim, s.d_state), dtype=sdt, device=dev)
     ptrs = None
     if init_states is not None:
+        if len(init_states) != int(plan.info.batch):
+            raise ValueError(f"init_states needs one entry per sequence ({plan.info.batch}), got {len(init_states)}")
         ptrs = []
         for st in init_states:
             if st is None:
                 ptrs.append(None)
             else:
-                if (not st.is_cuda or st.dtype != torch.float32 or not st.is_contiguous()
+                if (not st.is_cuda or st.dtype != sdt or not st.is_contiguous()
                         or tuple(st.shape) != (s.nheads, s.headdim, s.d_state)):
-                    raise ValueError("initial states must be contiguous fp32 CUDA [H,P,N] tensors")
+                    raise ValueError(f"initial states must be contiguous {sdt} CUDA [H,P,N] tensors")
                 ptrs.append(st.data_ptr())
-    ws_bytes = ssm_plan_workspace_bytes(plan.handle)
-    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=dev) if ws_bytes else None
+    ws = plan.workspace(dev)
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
-    ssm_prefill(plan.handle, x.data_ptr(), dt.data_ptr(), A.data_ptr(), B.data_ptr(), C.data_ptr(),
-                D.data_ptr(), ptrs, y_out.data_ptr(),
-                state_out.data_ptr() if state_out is not None else None,
-                ws.data_ptr() if ws is not None else None, ws_bytes, stream)
+    (entry or ssm_prefill)(plan.handle, x.data_ptr(), dt.data_ptr(), A.data_ptr(), B.data_ptr(), C.data_ptr(),
+                           D.data_ptr(), ptrs, y_out.data_ptr(),
+                           state_out.data_ptr() if state_out is not None else None,
+                           ws.data_ptr() if ws is not None else None, ws.numel() if ws is not None else 0, stream)
     return y_out, state_out

@@ -8,7 +8,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "libssm_prefill.so")
-SOURCES = ["plan.cpp", "api.hip", "scan_valu.hip", "scan_mfma.hip"]
+SOURCES = ["plan.cpp", "api.hip", "scan_valu.hip", "scan_mfma.hip", "state_advance.hip", "conv1d_prefill.hip"]
 
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = [

@@ -1,6 +1,3 @@
-// STATUS: candidate for a further entry point of the library.  It is not built into the library and has never run
-// on a GPU; it lives next to the CPU emulator so that the emulation tests can check it first.
-//
 // Causal depthwise convolution in front of the SSM scan, with cached-state resume and state checkpoints (the
 // conv_1d state of Appendix A.1, "Memory footprint").  For channel c, kernel width K <= 4 and the sequence-local
 // token t:

@@ -34,7 +34,28 @@ template <> struct IoTraits<bf16_t> {
     static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 };
 
-// Arguments common to both scan kernels.  Pointers are device pointers.
+// One element of a cached state in its storage type (ssm_state_dtype_t); the running state is always fp32 and a
+// reduced-precision checkpoint is that fp32 value rounded once, to nearest even.
+__device__ __forceinline__ float state_load(const void *base, size_t idx, int state_dtype)
+{
+    if (state_dtype == SSM_ST_F16)
+        return (float)static_cast<const _Float16 *>(base)[idx];
+    if (state_dtype == SSM_ST_BF16)
+        return bf16_to_f32(static_cast<const bf16_t *>(base)[idx]);
+    return static_cast<const float *>(base)[idx];
+}
+
+__device__ __forceinline__ void state_store(void *base, size_t idx, float v, int state_dtype)
+{
+    if (state_dtype == SSM_ST_F16)
+        static_cast<_Float16 *>(base)[idx] = (_Float16)v;
+    else if (state_dtype == SSM_ST_BF16)
+        static_cast<bf16_t *>(base)[idx] = f32_to_bf16(v);
+    else
+        static_cast<float *>(base)[idx] = v;
+}
+
+// Arguments common to the scan kernels.  Pointers are device pointers.
 struct ScanArgs {
     const void *x;
     const void *dt;
@@ -43,14 +64,23 @@ struct ScanArgs {
     const void *C;
     const float *D;
     void *y;
-    float *state_out;
-    const float *const *init_ptrs;  // [batch] or NULL
+    void *state_out;                // [n_ckpt,H,P,N] in the state type
+    const void *const *init_ptrs;   // [batch] pointers to [H,P,N] in the state type, or NULL
     const SsmTile *tiles;
     const SsmSeq *seqs;
     int32_t H, P, N, G;
     int32_t p_split;
+    int32_t state_dtype;            // ssm_state_dtype_t
 };
 
 // Launchers implemented next to their kernels.
 hipError_t launch_scan_valu(const ssm_plan *plan, const ScanArgs &args, hipStream_t stream);
-hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, hipStream_t stream);
+hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
+bool state_advance_supports(const ssm_shape_t &s);
+hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs,
+                                hipStream_t stream);
+bool conv1d_supports(int channels, int K, int io_dtype);
+hipError_t launch_conv1d_prefill(const ssm_plan *plan, const SsmTile *d_tiles, const SsmSeq *d_seqs, int channels,
+                                 int K, const void *in, const float *w, const float *bias,
+                                 const void *const *d_init_ptrs, void *out, void *state_out, int act,
+                                 hipStream_t stream);

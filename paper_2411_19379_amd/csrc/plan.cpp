@@ -73,6 +73,8 @@ extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
         return fail(SSM_ERR_INVALID_ARG, "ngroups must divide nheads");
     if (s.io_dtype != SSM_DT_F32 && s.io_dtype != SSM_DT_BF16)
         return fail(SSM_ERR_INVALID_ARG, "io_dtype must be SSM_DT_F32 or SSM_DT_BF16");
+    if (s.state_dtype != SSM_ST_F32 && s.state_dtype != SSM_ST_F16 && s.state_dtype != SSM_ST_BF16)
+        return fail(SSM_ERR_INVALID_ARG, "state_dtype must be SSM_ST_F32, SSM_ST_F16 or SSM_ST_BF16");
     if (s.chunk < 16 || s.chunk > 256 || s.chunk % 16 != 0)
         return fail(SSM_ERR_UNSUPPORTED_SHAPE, "chunk must be a multiple of 16 in 16..256");
     if (s.nheads > 65535)

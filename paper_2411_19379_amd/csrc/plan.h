@@ -3,6 +3,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -34,11 +35,17 @@ struct ssm_plan {
     int32_t n_workgroups = 0;
     std::vector<SsmTile> tiles;
     std::vector<SsmSeq> seqs;
-    // device copies, made by the first ssm_prefill call
-    int device = -1;
-    void *d_tiles = nullptr;      // SsmTile[n_tiles]
-    void *d_seqs = nullptr;       // SsmSeq[batch]
-    void *d_init_ptrs = nullptr;  // const float*[batch], refreshed by every call
+    // Device copies of the two tables and a buffer for the per-call state
+    // pointers, one set per GPU the plan has been used on.  A cache behind a
+    // logically constant plan: filled on first use under `mu`.
+    struct DeviceTables {
+        int device = -1;
+        void *tiles = nullptr;  // SsmTile[n_tiles]
+        void *seqs = nullptr;   // SsmSeq[batch]
+        void *ptrs = nullptr;   // void*[batch], rewritten by every call that passes states
+    };
+    mutable std::mutex mu;
+    mutable std::vector<DeviceTables> device_tables;
 };
 
 void ssm_set_error(const std::string &msg);

@@ -601,7 +601,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
 
 }  // namespace
 
-hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, hipStream_t stream)
+hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *, hipStream_t stream)
 {
     static bool attr_set = false;
     const size_t lds = sizeof(Lds);
@@ -617,7 +617,8 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, hipStrea
     hipLaunchKernelGGL(ssm_scan_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
                        static_cast<const bf16_t *>(args.x), static_cast<const bf16_t *>(args.dt), args.A,
                        static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C), args.D,
-                       static_cast<bf16_t *>(args.y), args.state_out, args.init_ptrs, args.tiles, args.seqs,
+                       static_cast<bf16_t *>(args.y), static_cast<float *>(args.state_out),
+                       reinterpret_cast<const float *const *>(args.init_ptrs), args.tiles, args.seqs,
                        args.H, args.P, args.G, args.p_split, per_xcd, n_wg);
     return hipGetLastError();
 }

@@ -50,14 +50,15 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_valu_kernel(ScanArgs a)
 
     // running state: element e = tid + k*256 of this head's [P,N] block
     float acc[EPT];
-    const float *init = a.init_ptrs ? a.init_ptrs[seq] : nullptr;
+    const void *init = a.init_ptrs ? a.init_ptrs[seq] : nullptr;
+    const int st = a.state_dtype;
 #pragma unroll
     for (int k = 0; k < EPT; ++k) {
         const int e = tid + k * kThreads;
         float v = 0.f;
         if (e < PN) {
             if (init)
-                v = init[(size_t)h * PN + e];
+                v = state_load(init, (size_t)h * PN + e, st);
             S_lds[(e / N) * NP1 + (e % N)] = v;
         }
         acc[k] = v;
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_valu_kernel(ScanArgs a)
                 acc[k] = s;
                 S_lds[p * NP1 + n] = s;
                 if (t.ckpt_slot >= 0)
-                    a.state_out[((size_t)t.ckpt_slot * H + h) * PN + e] = s;
+                    state_store(a.state_out, ((size_t)t.ckpt_slot * H + h) * PN + e, s, st);
             }
         }
         __syncthreads();

@@ -1,6 +1,3 @@
-// STATUS: candidate for a further entry point of the library.  It is not built into the library and has never run
-// on a GPU; it lives next to the CPU emulator so that the emulation tests can check it first.
-//
 // Roll-forward of cached states (Section 4.1: a kernel that rolls a checkpointed state forward by a few tokens to
 // reach an exact position; with one token per sequence it is the decode step).  Every sequence of the batch brings
 // its own [H,P,N] state (fp32, or fp16 / bf16 as a cache stores it), which is advanced IN PLACE by the sequence's
@@ -64,7 +61,7 @@ template <> struct Vec4<bf16_t> {
 // Storage type of the cached states: fp32, or fp16 / bf16 as a cache keeps them (Section 5.1: FP16 everywhere;
 // Appendix A.1: 2 bytes per state element), which halves the bytes this kernel moves.  Arithmetic stays fp32; a
 // reduced-precision state is rounded once, to nearest even, when it is written back.
-enum { ADV_STATE_F32 = 0, ADV_STATE_F16 = 1, ADV_STATE_BF16 = 2 };
+enum { ADV_STATE_F32 = SSM_ST_F32, ADV_STATE_F16 = SSM_ST_F16, ADV_STATE_BF16 = SSM_ST_BF16 };
 template <int ST> struct StateVec;
 template <> struct StateVec<ADV_STATE_F32> {
     typedef float elem;
@@ -225,11 +222,12 @@ bool state_advance_supports(const ssm_shape_t &s)
 }
 
 // Advance the state of every sequence of the plan in place by the sequence's tokens; `d_state_ptrs` is a device array
-// of plan->batch device pointers to states of type `state_type` (0 fp32, 1 fp16, 2 bf16).  y may be null.
+// of plan->batch device pointers to states in the plan's state type.  y may be null.
 // Checkpoints of the plan are ignored (the result is the in-place state after the last token).
-hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs, int state_type,
+hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs,
                                 hipStream_t stream)
 {
+    const int state_type = args.state_dtype;
     if (!state_advance_supports(plan->shape) || state_type < ADV_STATE_F32 || state_type > ADV_STATE_BF16)
         return hipErrorInvalidValue;
     if (plan->batch == 0 || plan->tiles.empty())

@@ -1,6 +1,5 @@
 // Spot check of the matrix-core scan kernel at full problem sizes on the emulator (test infrastructure only): only
-// the first two and the last workgroup of the scan run (and, for the candidate, the score-block workgroups they
-// depend on), every buffer is guarded, and the outputs of those workgroups are compared with a plain fp64 recurrence
+// the first two and the last workgroup of the scan run, every buffer is guarded, and the outputs of those workgroups are compared with a plain fp64 recurrence
 // computed here.  Inputs are drawn only where those workgroups read them.   emu_big <T> <ckpt_every> [H P G]
 #include <hip/hip_runtime.h>
 #include <cmath>
@@ -10,24 +9,12 @@
 #include "device_utils.h"
 #include "emu_host.h"
 namespace emu { void set_order_mode(int m); void set_block_filter(bool (*)(int, unsigned)); long switches(); }
-#ifdef SSM_EMU_CANDIDATE
-size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
-hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream, int state_type);
-#endif
 
 static int gH, gP, gG, g_per_xcd, g_psplit;
 static std::vector<int> g_wgs;   // logical workgroup ids to run
 static bool filter(int launch, unsigned b)
 {
-#ifdef SSM_EMU_CANDIDATE
-    if (launch == 0) {  // score blocks: block = tile * G + g; keep the groups of the selected heads
-        const int g = b % gG;
-        for (int wg : g_wgs) if (((wg / g_psplit) % gH) / (gH / gG) == g) return true;
-        return false;
-    }
-#else
     (void)launch;
-#endif
     const int wg = (b & 7) * g_per_xcd + (b >> 3);
     for (int w : g_wgs) if (w == wg) return true;
     return false;
@@ -40,7 +27,7 @@ int main(int argc, char **argv)
     const int T = argc > 1 ? atoi(argv[1]) : 4096, every = argc > 2 ? atoi(argv[2]) : 4096;
     const int H = argc > 3 ? atoi(argv[3]) : 128, P = argc > 4 ? atoi(argv[4]) : 64, G = argc > 5 ? atoi(argv[5]) : 8, N = 128;
     gH = H; gP = P; gG = G;
-    ssm_shape_t sh = {H, P, N, G, 256, SSM_DT_BF16};
+    ssm_shape_t sh = {H, P, N, G, 256, SSM_DT_BF16, SSM_ST_F32};
     std::vector<int32_t> ck; for (int p = every; p <= T; p += every) ck.push_back(p);
     int32_t cu[2] = {0, T}, cuck[2] = {0, (int32_t)ck.size()};
     ssm_plan_t *plan; if (ssm_plan_create(&sh, 1, cu, cuck, ck.data(), &plan)) { printf("plan: %s\n", ssm_last_error()); return 1; }
@@ -70,14 +57,11 @@ int main(int argc, char **argv)
     SsmSeq *seqs = (SsmSeq *)guarded(sizeof(SsmSeq), true);
     memcpy(tiles, plan->tiles.data(), plan->tiles.size() * sizeof(SsmTile)); memcpy(seqs, plan->seqs.data(), sizeof(SsmSeq));
     ScanArgs a; a.x = x; a.dt = dt; a.A = A; a.B = B; a.C = C; a.D = D; a.y = y; a.state_out = st; a.init_ptrs = nullptr;
-    a.tiles = tiles; a.seqs = seqs; a.H = H; a.P = P; a.N = N; a.G = G; a.p_split = plan->p_split;
+    a.tiles = tiles; a.seqs = seqs; a.H = H; a.P = P; a.N = N; a.G = G; a.p_split = plan->p_split; a.state_dtype = SSM_ST_F32;
     emu::set_order_mode(1); emu::set_block_filter(filter);
-#ifdef SSM_EMU_CANDIDATE
-    void *ws = guarded(scan_mfma_next_workspace_bytes(plan), true);
-    if (launch_scan_mfma_next(plan, a, ws, nullptr, 0) != hipSuccess) { printf("launch failed\n"); return 1; }
-#else
-    if (launch_scan_mfma(plan, a, nullptr) != hipSuccess) { printf("launch failed\n"); return 1; }
-#endif
+    size_t ws_bytes = 0; ssm_plan_workspace_bytes(plan, &ws_bytes);
+    void *ws = guarded(ws_bytes ? ws_bytes : 16, true);
+    if (launch_scan_mfma(plan, a, ws, nullptr) != hipSuccess) { printf("launch failed\n"); return 1; }
     printf("emulated %zu workgroups, %ld fiber switches\n", g_wgs.size(), emu::switches());
     double worst_y = 0, worst_s = 0;
     for (int wg : g_wgs) {

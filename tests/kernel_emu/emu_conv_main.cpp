@@ -1,4 +1,4 @@
-// Driver of the CPU emulation for the convolution candidate (test infrastructure only): reads a problem file, builds
+// Driver of the CPU emulation for the convolution kernel (test infrastructure only): reads a problem file, builds
 // the scan's plan for the layer shape (the convolution walks the same tile table), runs the CPU-compiled kernel on
 // fibers and writes the outputs and the checkpointed states.  Buffers are guarded as in emu_main.cpp.
 //   emu_conv_main <in.bin> <out.bin> [order] [end|start]
@@ -15,11 +15,6 @@ namespace emu {
 void set_order_mode(int m);
 long switches();
 }  // namespace emu
-
-hipError_t launch_conv1d_prefill(const ssm_plan *plan, const SsmTile *d_tiles, const SsmSeq *d_seqs, int channels,
-                                 int K, const void *in, const float *w, const float *bias,
-                                 const void *const *d_init_ptrs, void *out, void *state_out, int act,
-                                 hipStream_t stream);
 
 int main(int argc, char **argv)
 {
@@ -72,6 +67,7 @@ int main(int argc, char **argv)
 
     ssm_shape_t shape;
     shape.nheads = H, shape.headdim = P, shape.d_state = N, shape.ngroups = G, shape.chunk = chunk, shape.io_dtype = io;
+    shape.state_dtype = SSM_ST_F32;
     ssm_plan_t *plan = nullptr;
     int rc = ssm_plan_create(&shape, batch, cu.data(), cu_ck.data(), ck.data(), &plan);
     if (rc != 0) {

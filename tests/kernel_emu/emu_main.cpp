@@ -4,25 +4,15 @@
 //   emu_main <in.bin> <out.bin> [order: 0 forward | 1 reverse | n>=2 shuffle seed] [end|start] [drop_barrier]
 //   "end"/"start": which end of each buffer touches the inaccessible page (overruns / underruns fault)
 //   drop_barrier: ordinal of one workgroup barrier that is made not to wait (self-test of the race check; -1: none)
-//   a 6th argument "advance" (candidate build only) runs the roll-forward kernel instead: every sequence's state
-//   (its initial state, or zeros) is advanced in place, and the output holds y and then one state per sequence;
-//   a 7th argument f16 or bf16 keeps the states in that type (converted from and to fp32 around the run)
+//   a 6th argument "advance" runs the roll-forward kernel instead of the scan: every sequence's state (its initial
+//   state, or zeros) is advanced in place, and the output holds y and then one state per sequence;
+//   a 7th argument f16 or bf16 keeps cached states in that type (converted from and to fp32 around the run)
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
 
 #include "device_utils.h"
-
-#ifdef SSM_EMU_CANDIDATE
-// the candidate revision of the matrix-core kernel (tests/kernel_emu/candidate) takes a workspace
-size_t scan_mfma_next_workspace_bytes(const ssm_plan *plan);
-hipError_t launch_scan_mfma_next(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream,
-                                 int state_type);
-// the candidate roll-forward entry: states advanced in place
-hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs, int state_type,
-                                hipStream_t stream);
-#endif
 
 namespace emu {
 void set_order_mode(int m);
@@ -103,6 +93,7 @@ int main(int argc, char **argv)
 
     ssm_shape_t shape;
     shape.nheads = H, shape.headdim = P, shape.d_state = N, shape.ngroups = G, shape.chunk = chunk, shape.io_dtype = io;
+    shape.state_dtype = st_type;
     ssm_plan_t *plan = nullptr;
     int rc = ssm_plan_create(&shape, batch, cu.data(), cu_ck.data(), ck.data(), &plan);
     if (rc != 0) {
@@ -122,18 +113,18 @@ int main(int argc, char **argv)
 
     ScanArgs args;
     args.x = x, args.dt = dt, args.A = A, args.B = B, args.C = C, args.D = D, args.y = y, args.state_out = st;
-    args.init_ptrs = any_init ? init : nullptr;
+    args.init_ptrs = any_init ? reinterpret_cast<const void *const *>(init) : nullptr;
     args.tiles = tiles, args.seqs = seqs;
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
+    args.state_dtype = st_type;
     if (advance) {
-#ifdef SSM_EMU_CANDIDATE
         void **sp = static_cast<void **>(guarded(sizeof(void *) * (batch ? batch : 1), end_aligned));
         for (int b = 0; b < batch; ++b) {
             sp[b] = guarded(nst * st_esz, end_aligned);
             for (size_t e = 0; e < nst; ++e)
                 to_state(sp[b], e, init[b] ? init[b][e] : 0.f);
         }
-        if (launch_state_advance(plan, args, sp, st_type, nullptr) != hipSuccess) {
+        if (launch_state_advance(plan, args, sp, nullptr) != hipSuccess) {
             fprintf(stderr, "launch_state_advance failed\n");
             return 2;
         }
@@ -148,49 +139,37 @@ int main(int argc, char **argv)
         fclose(f);
         printf("emu ok: advance, %d sequences, %ld fiber switches\n", batch, emu::switches());
         return 0;
-#else
-        fprintf(stderr, "advance mode needs the candidate build\n");
-        return 2;
-#endif
     }
     if (plan->n_workgroups > 0 && T > 0) {
-#ifdef SSM_EMU_CANDIDATE
-        hipError_t e;
-        if (plan->path == SSM_PATH_MFMA_BF16) {
-            const size_t ws_bytes = scan_mfma_next_workspace_bytes(plan);
-            void *ws = guarded(ws_bytes ? ws_bytes : 16, end_aligned);
-            memset(ws, 0xFF, ws_bytes);
-            if (st_type != 0) {
-                // cached states in the reduced type: convert the initial ones, give the kernel a checkpoint buffer of
-                // that type, and convert the checkpoints back to fp32 for the output file
-                for (int b = 0; b < batch; ++b)
-                    if (init[b]) {
-                        void *conv = guarded(nst * st_esz, end_aligned);
-                        for (size_t k = 0; k < nst; ++k)
-                            to_state(conv, k, init[b][k]);
-                        init[b] = static_cast<const float *>(conv);
-                    }
-                const size_t nck = (size_t)(n_ckpt ? n_ckpt : 1) * nst;
-                void *st_red = guarded(nck * st_esz, end_aligned);
-                memset(st_red, 0xFF, nck * st_esz);
-                args.state_out = static_cast<float *>(st_red);
-                e = launch_scan_mfma_next(plan, args, ws, nullptr, st_type);
-                for (size_t k = 0; k < (size_t)n_ckpt * nst; ++k)
-                    st[k] = from_state(st_red, k);
-            } else {
-                e = launch_scan_mfma_next(plan, args, ws, nullptr, 0);
-            }
-        } else {
-            e = launch_scan_valu(plan, args, nullptr);
+        size_t ws_bytes = 0;
+        ssm_plan_workspace_bytes(plan, &ws_bytes);
+        void *ws = guarded(ws_bytes ? ws_bytes : 16, end_aligned);
+        memset(ws, 0xFF, ws_bytes);
+        void *st_red = nullptr;
+        if (st_type != 0) {
+            // cached states in the reduced type: convert the initial ones, give the kernel a checkpoint buffer of
+            // that type, and convert the checkpoints back to fp32 for the output file
+            for (int b = 0; b < batch; ++b)
+                if (init[b]) {
+                    void *conv = guarded(nst * st_esz, end_aligned);
+                    for (size_t k = 0; k < nst; ++k)
+                        to_state(conv, k, init[b][k]);
+                    init[b] = static_cast<const float *>(conv);
+                }
+            const size_t nck = (size_t)(n_ckpt ? n_ckpt : 1) * nst;
+            st_red = guarded(nck * st_esz, end_aligned);
+            memset(st_red, 0xFF, nck * st_esz);
+            args.state_out = st_red;
         }
-#else
-        const hipError_t e = plan->path == SSM_PATH_MFMA_BF16 ? launch_scan_mfma(plan, args, nullptr)
+        const hipError_t e = plan->path == SSM_PATH_MFMA_BF16 ? launch_scan_mfma(plan, args, ws, nullptr)
                                                               : launch_scan_valu(plan, args, nullptr);
-#endif
         if (e != hipSuccess) {
             fprintf(stderr, "launch failed\n");
             return 2;
         }
+        if (st_red)
+            for (size_t k = 0; k < (size_t)n_ckpt * nst; ++k)
+                st[k] = from_state(st_red, k);
     }
     f = fopen(argv[2], "wb");
     fwrite(y, esz, nx, f);

@@ -17,9 +17,8 @@ layouts) and driven on seeded workloads.  Checked:
   shows up as a non-finite result;
 * the checker itself: with one barrier made not to wait, the orders disagree.
 
-The same checks run on the candidates in `tests/kernel_emu/candidate/` (the next revision of the matrix-core
-kernel and a roll-forward kernel that advances cached states in place), which are not built into the library and
-have not run on a GPU yet.
+The same checks run on the roll-forward kernel (`state_advance.hip`) and on the convolution in front of the scan
+(`conv1d_prefill.hip`).
 
 The only edits to the kernel sources are textual and listed in `_convert`: the
 two LDS-wait/barrier instructions become emulator calls and the dynamic LDS
@@ -68,8 +67,9 @@ def _build(tmp_path_factory, name, mfma_source, extra_flags=(), extra_sources=()
     _convert(os.path.join(CSRC, "scan_valu.hip"), os.path.join(d, "scan_valu.cpp"))
     flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
              "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags]
-    srcs = [os.path.join(d, "scan_mfma.cpp"), os.path.join(d, "scan_valu.cpp"), os.path.join(CSRC, "plan.cpp"),
-            os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_main.cpp")]
+    _convert(os.path.join(CSRC, "state_advance.hip"), os.path.join(d, "state_advance.cpp"))
+    srcs = [os.path.join(d, "scan_mfma.cpp"), os.path.join(d, "scan_valu.cpp"), os.path.join(d, "state_advance.cpp"),
+            os.path.join(CSRC, "plan.cpp"), os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_main.cpp")]
     for k, src in enumerate(extra_sources):
         _convert(src, os.path.join(d, f"extra{k}.cpp"))
         srcs.append(os.path.join(d, f"extra{k}.cpp"))
@@ -95,11 +95,11 @@ def emu_binary(tmp_path_factory):
 
 @pytest.fixture(scope="session")
 def emu_conv_binary(tmp_path_factory):
-    """The convolution candidate with its own driver."""
+    """The convolution kernel with its own driver."""
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ with bf16 vector support found")
     d = str(tmp_path_factory.mktemp("kernel_emu_conv"))
-    _convert(os.path.join(EMU, "candidate", "conv1d_prefill.hip"), os.path.join(d, "conv1d_prefill.cpp"))
+    _convert(os.path.join(CSRC, "conv1d_prefill.hip"), os.path.join(d, "conv1d_prefill.cpp"))
     flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
              "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     srcs = [os.path.join(d, "conv1d_prefill.cpp"), os.path.join(CSRC, "plan.cpp"), os.path.join(EMU, "emu_rt.cpp"),
@@ -107,13 +107,6 @@ def emu_conv_binary(tmp_path_factory):
     out = os.path.join(d, "emu_conv_main")
     subprocess.run([CLANG, *flags, *srcs, "-o", out], check=True, capture_output=True)
     return out
-
-
-@pytest.fixture(scope="session")
-def emu_candidate_binary(tmp_path_factory):
-    """The candidate revision of the matrix-core kernel (not built into the library) beside the shipped fp32 one."""
-    return _build(tmp_path_factory, "kernel_emu_candidate", os.path.join(EMU, "candidate", "scan_mfma_next.hip"),
-                  ["-DSSM_EMU_CANDIDATE"], [os.path.join(EMU, "candidate", "state_advance.hip")])
 
 
 def _write_problem(path, wl, init_states):
@@ -228,29 +221,6 @@ def test_emulated_kernel_matches_oracle_in_any_wave_order(emu_binary, tmp_path, 
     _check_case(emu_binary, tmp_path, io, case)
 
 
-@pytest.mark.parametrize("case", sorted(CASES))
-def test_candidate_kernel_matches_oracle_in_any_wave_order(emu_candidate_binary, tmp_path, case):
-    """The candidate carries the decay-weighted x as a bf16 pair, so its checkpoints are held to 1e-4 where it runs
-    (the "odd" shape falls to the fp32 vector kernel as before)."""
-    _check_case(emu_candidate_binary, tmp_path, "bf16", case, state_tol=1e-4)
-
-
-@pytest.fixture(scope="session")
-def emu_candidate_split_binary(tmp_path_factory):
-    """The candidate with its optional paths on: the bf16 copy of S carried as a pair as well, y stored one step
-    late by the output waves, raised wave priorities (a no-op here)."""
-    return _build(tmp_path_factory, "kernel_emu_candidate_split",
-                  os.path.join(EMU, "candidate", "scan_mfma_next.hip"),
-                  ["-DSSM_EMU_CANDIDATE", "-DSSM_SS_SPLIT=1", "-DSSM_DEFER_Y=1", "-DSSM_WAVE_PRIO=1"],
-                  [os.path.join(EMU, "candidate", "state_advance.hip")])
-
-
-@pytest.mark.parametrize("case", ["ragged", "p32_groups", "empty_seq", "tiny", "long"])
-def test_candidate_with_state_copy_split(emu_candidate_split_binary, tmp_path, case):
-    """With both pairs on, y after a resume from an O(1) cached state stays within half the bf16 budget."""
-    _check_case(emu_candidate_split_binary, tmp_path, "bf16", case, state_tol=1e-4, y_tol=1e-2)
-
-
 ADVANCE_CASES = {
     # decode step: one token per sequence, some sequences with a cached state, some from zero
     "decode": ((4, 64, 128, 2, 64), [1, 1, 1, 1, 1]),
@@ -265,8 +235,8 @@ ADVANCE_CASES = {
 
 @pytest.mark.parametrize("io", ["bf16", "f32"])
 @pytest.mark.parametrize("case", sorted(ADVANCE_CASES))
-def test_candidate_state_advance_matches_oracle(emu_candidate_binary, tmp_path, io, case):
-    """The roll-forward candidate: states advanced in place and y against the oracle started from the same states.
+def test_state_advance_matches_oracle(emu_binary, tmp_path, io, case):
+    """The roll-forward kernel: states advanced in place and y against the oracle started from the same states.
     All arithmetic is fp32, so states are held to 1e-5 whatever the storage type; y carries its storage rounding."""
     (H, P, N, G, chunk), seqlens = ADVANCE_CASES[case]
     shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype=io)
@@ -281,7 +251,7 @@ def test_candidate_state_advance_matches_oracle(emu_candidate_binary, tmp_path, 
     y_ref, st_ref = _oracle(wl, init)
     first = None
     for order, align in ((0, "end"), (1, "start")):
-        y, st, raw = _emulate(emu_candidate_binary, wl, init, tmp_path, order, align, advance=True)
+        y, st, raw = _emulate(emu_binary, wl, init, tmp_path, order, align, advance=True)
         assert np.all(np.isfinite(y)) and np.all(np.isfinite(st))
         assert max(rel_err(y, y_ref)) <= (5e-3 if io == "bf16" else 1e-5)
         k = 0
@@ -308,7 +278,7 @@ CONV_CASES = {
 @pytest.mark.parametrize("K", [1, 2, 4])
 @pytest.mark.parametrize("io", ["bf16", "f32"])
 @pytest.mark.parametrize("case", sorted(CONV_CASES))
-def test_candidate_conv1d_matches_oracle(emu_conv_binary, tmp_path, io, case, K):
+def test_conv1d_matches_oracle(emu_conv_binary, tmp_path, io, case, K):
     """Outputs against the convolution oracle from the same cached states; checkpointed states are copies of
     inputs and must be bit-exact."""
     from oracle import conv1d_prefill_oracle
@@ -361,7 +331,7 @@ def test_candidate_conv1d_matches_oracle(emu_conv_binary, tmp_path, io, case, K)
 
 
 @pytest.mark.parametrize("state_type,ulp", [("f16", 2.0 ** -10), ("bf16", 2.0 ** -7)])
-def test_candidate_state_advance_with_reduced_precision_states(emu_candidate_binary, tmp_path, state_type, ulp):
+def test_state_advance_with_reduced_precision_states(emu_binary, tmp_path, state_type, ulp):
     """States kept as a cache stores them (Section 5.1: FP16): read, advanced in fp32, rounded once on the way back.
     Expected: the oracle's state from the same (representable) start, to one unit in the last place of the type."""
     (H, P, N, G, chunk), seqlens = (4, 64, 128, 2, 64), [1, 7, 0, 2]
@@ -376,7 +346,7 @@ def test_candidate_state_advance_with_reduced_precision_states(emu_candidate_bin
     init = [None if v is None else v.to(tdt).float() for v in wl.init_state]   # representable starts
     wl.init_state = init
     y_ref, st_ref = _oracle(wl, init)
-    y, st, _ = _emulate(emu_candidate_binary, wl, init, tmp_path, 0, "end", advance=True, state_type=state_type)
+    y, st, _ = _emulate(emu_binary, wl, init, tmp_path, 0, "end", advance=True, state_type=state_type)
     assert max(rel_err(y, y_ref)) <= 5e-3
     k = 0
     for b, n in enumerate(seqlens):
@@ -391,41 +361,17 @@ def test_candidate_state_advance_with_reduced_precision_states(emu_candidate_bin
             k += 1
 
 
-@pytest.mark.parametrize("state_type,ulp", [("f16", 2.0 ** -10), ("bf16", 2.0 ** -7)])
-def test_candidate_scan_with_reduced_precision_states(emu_candidate_binary, tmp_path, state_type, ulp):
-    """The scan candidate with cached states stored as fp16 / bf16: initial states are read in that type, the running
-    state stays fp32, checkpoints are rounded once.  Against the oracle from the same representable initial states:
-    y as usual, checkpoints to one unit in the last place of the type on top of the kernel's own error."""
-    (H, P, N, G, chunk), cfg, kw = CASES["ragged"]
-    shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype="bf16")
-    wl = make_workload(cfg, "cpu", seed=11, shape=shape, **kw)
-    tdt = torch.float16 if state_type == "f16" else torch.bfloat16
-    init = [None if v is None else v.to(tdt).float() for v in wl.init_state]
-    wl.init_state = init
-    y_ref, st_ref = _oracle(wl, init)
-    y, st, _ = _emulate(emu_candidate_binary, wl, init, tmp_path, 1, "end", state_type=state_type)
-    assert np.all(np.isfinite(y)) and np.all(np.isfinite(st))
-    assert max(rel_err(y, y_ref)) <= TOL["bf16"]
-    rms = float(np.sqrt(np.mean(st_ref * st_ref)))
-    assert np.all(np.abs(st - st_ref) <= ulp * np.maximum(np.abs(st_ref), rms) + 1e-4 * rms)
-    assert np.array_equal(torch.from_numpy(st.copy()).to(tdt).float().numpy(), st)
-
-
-@pytest.mark.parametrize("which", ["shipped", "candidate"])
-def test_full_size_spot_check(tmp_path_factory, which):
+def test_full_size_spot_check(tmp_path_factory):
     """The 7B-shaped 32K-token configuration (H=128, P=64, N=128, G=8, one checkpoint at the end) on the emulator:
     only the first two and the last workgroup run, on guarded buffers of the full size, and are compared with a
     plain fp64 recurrence inside the driver.  Token offsets, group indexing and the workgroup renumbering are the
     real ones."""
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ with bf16 vector support found")
-    d = str(tmp_path_factory.mktemp("kernel_emu_big_" + which))
-    src = os.path.join(CSRC, "scan_mfma.hip") if which == "shipped" else os.path.join(EMU, "candidate", "scan_mfma_next.hip")
-    _convert(src, os.path.join(d, "scan_mfma.cpp"))
+    d = str(tmp_path_factory.mktemp("kernel_emu_big"))
+    _convert(os.path.join(CSRC, "scan_mfma.hip"), os.path.join(d, "scan_mfma.cpp"))
     flags = ["-std=c++17", "-O2", "-fno-strict-aliasing", "-ffp-contract=off", "-Wno-psabi", "-Wno-unused-value",
              "-I", EMU, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    if which == "candidate":
-        flags.append("-DSSM_EMU_CANDIDATE")
     out = os.path.join(d, "emu_big")
     r = subprocess.run([CLANG, *flags, os.path.join(d, "scan_mfma.cpp"), os.path.join(CSRC, "plan.cpp"),
                         os.path.join(EMU, "emu_rt.cpp"), os.path.join(EMU, "emu_big.cpp"), "-o", out],
