@@ -168,6 +168,32 @@ int ssm_prefill(const ssm_plan_t *plan,
                 void *hip_stream);
 
 /*
+ * ssm_prefill for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results and same errors as ssm_prefill, but the plan's tile
+ * and sequence tables and the initial-state pointers are written (by small
+ * kernels on `hip_stream`) into a fixed device array that is part of the
+ * library image instead of buffers allocated on a plan's first use.  The call
+ * makes no hipMalloc, hipFree, memory copy or other allocating call, never
+ * synchronises, and touches nothing of the plan.
+ *
+ * Limits: at most 16384 tiles (ssm_plan_info n_tiles) and 1024 sequences per
+ * call, otherwise SSM_ERR_UNSUPPORTED_SHAPE and nothing is enqueued.  The
+ * array (272 KiB per GPU the library runs on, held until the process ends) is
+ * shared by every call on that GPU: calls that overlap on one GPU, on
+ * different streams, race.  Calls on one stream are ordered by the stream.
+ * Every call rewrites all it reads of the array, so nothing carries over from
+ * one call to the next.
+ */
+int ssm_prefill_noalloc(const ssm_plan_t *plan,
+                        const void *x, const void *dt, const float *A,
+                        const void *B, const void *C, const float *D,
+                        const void *const *init_state_ptrs,
+                        void *y_out, void *state_out,
+                        void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+/*
  * Roll cached states forward (Section 4.1, "Obtaining states during
  * prefill": a kernel that rolls a checkpointed state forward by a few tokens
  * to reach an exact position); with one token per sequence it is the decode

@@ -24,5 +24,6 @@ from .binding import (  # noqa: F401
     ssm_plan_workspace_bytes,
     ssm_conv1d_prefill,
     ssm_prefill,
+    ssm_prefill_noalloc,
     ssm_state_advance,
 )

@@ -80,6 +80,8 @@ def load_library():
     lib.ssm_prefill.restype = ctypes.c_int
     lib.ssm_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp,
                                 ctypes.c_size_t, vp]
+    lib.ssm_prefill_noalloc.restype = ctypes.c_int
+    lib.ssm_prefill_noalloc.argtypes = lib.ssm_prefill.argtypes
     lib.ssm_state_advance.restype = ctypes.c_int
     lib.ssm_state_advance.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp]
     lib.ssm_conv1d_prefill.restype = ctypes.c_int
@@ -165,6 +167,14 @@ def ssm_prefill(plan: int, x: int, dt: int, A: int, B: int, C: int, D: int,
     """Raw call: every tensor argument is a device address (int)."""
     _check(load_library().ssm_prefill(plan, x, dt, A, B, C, D, _ptr_array(plan, init_state_ptrs), y_out, state_out,
                                       workspace, workspace_bytes, hip_stream))
+
+
+def ssm_prefill_noalloc(plan: int, x: int, dt: int, A: int, B: int, C: int, D: int,
+                        init_state_ptrs: Optional[Sequence[Optional[int]]], y_out: int, state_out: Optional[int],
+                        workspace: Optional[int], workspace_bytes: int, hip_stream: Optional[int]):
+    """Raw call of the entry point that allocates nothing; arguments as ssm_prefill."""
+    _check(load_library().ssm_prefill_noalloc(plan, x, dt, A, B, C, D, _ptr_array(plan, init_state_ptrs), y_out,
+                                              state_out, workspace, workspace_bytes, hip_stream))
 
 
 def ssm_state_advance(plan: int, x: int, dt: int, A: int, B: int, C: int, D: int,

@@ -124,7 +124,7 @@ static int check_state_ptrs(const ssm_plan *plan, const void *const *ptrs, bool 
     return SSM_OK;
 }
 
-// Checks of ssm_prefill.  *any_init: a non-null initial state was passed.
+// Checks shared by ssm_prefill and ssm_prefill_noalloc.  *any_init: a non-null initial state was passed.
 static int check_prefill(const ssm_plan *plan, const void *x, const void *dt, const float *A, const void *B,
                          const void *C, const float *D, const void *const *init_state_ptrs, void *y_out,
                          void *state_out, void *workspace, size_t workspace_bytes, bool *any_init)
@@ -218,6 +218,80 @@ extern "C" int ssm_prefill(const ssm_plan_t *plan,
     }
     return launch_scan(plan, x, dt, A, B, C, D, y_out, state_out, workspace, t.tiles, t.seqs,
                        any_init ? t.ptrs : nullptr, stream);
+}
+
+// ---------------------------------------------------------------- the scan for callers that cannot allocate
+// The plan's tile table, its sequence table and the per-call state pointers go into a fixed device array that is
+// part of the library image, in place of the buffers ssm_prefill allocates on a plan's first use.  Every call on a
+// GPU shares that GPU's array: calls that overlap on one GPU race.  All three tables are rewritten by every call, so
+// nothing of an earlier call is read.
+constexpr size_t kNoAllocMaxTiles = 16384;
+constexpr size_t kNoAllocMaxBatch = 1024;
+constexpr size_t kScratchSeqsOff = kNoAllocMaxTiles * sizeof(SsmTile);
+constexpr size_t kScratchPtrsOff = kScratchSeqsOff + kNoAllocMaxBatch * sizeof(SsmSeq);
+constexpr size_t kScratchBytes = kScratchPtrsOff + kNoAllocMaxBatch * sizeof(void *);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static unsigned char *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, set on first use there
+static std::mutex g_scratch_mutex;
+
+static int scratch_on_current_device(unsigned char **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail("hipGetDevice", e);
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(SSM_ERR_INVALID_ARG, "device ordinal above 63");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return hip_fail("hipGetSymbolAddress(scratch)", e);
+        if (!ptr)
+            return fail(SSM_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return SSM_OK;
+}
+
+extern "C" int ssm_prefill_noalloc(const ssm_plan_t *plan,
+                                   const void *x, const void *dt, const float *A,
+                                   const void *B, const void *C, const float *D,
+                                   const void *const *init_state_ptrs,
+                                   void *y_out, void *state_out,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    if (!plan)
+        return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->total_tokens == 0 || plan->batch == 0)
+        return SSM_OK;
+    if (plan->tiles.size() > kNoAllocMaxTiles || (size_t)plan->batch > kNoAllocMaxBatch)
+        return fail(SSM_ERR_UNSUPPORTED_SHAPE,
+                    "ssm_prefill_noalloc handles at most 16384 tiles and 1024 sequences per call");
+    bool any_init = false;
+    int rc = check_prefill(plan, x, dt, A, B, C, D, init_state_ptrs, y_out, state_out, workspace, workspace_bytes,
+                           &any_init);
+    if (rc != SSM_OK)
+        return rc;
+    unsigned char *base = nullptr;
+    rc = scratch_on_current_device(&base);
+    if (rc != SSM_OK)
+        return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = upload_table(base, plan->tiles.data(), plan->tiles.size() * sizeof(SsmTile), stream);
+    if (e == hipSuccess)
+        e = upload_table(base + kScratchSeqsOff, plan->seqs.data(), plan->seqs.size() * sizeof(SsmSeq), stream);
+    if (e == hipSuccess && any_init)
+        e = upload_table(base + kScratchPtrsOff, init_state_ptrs, (size_t)plan->batch * sizeof(void *), stream);
+    if (e != hipSuccess)
+        return hip_fail("upload of the plan's tables into the fixed device array", e);
+    return launch_scan(plan, x, dt, A, B, C, D, y_out, state_out, workspace, base, base + kScratchSeqsOff,
+                       any_init ? base + kScratchPtrsOff : nullptr, stream);
 }
 
 // ---------------------------------------------------------------- roll-forward / decode step

@@ -1,0 +1,51 @@
+"""ssm_prefill_noalloc against ssm_prefill through the C ABI: two calls in a row, the second with a smaller input.
+The file name sorts last so that a failure here hides no other test."""
+import pytest
+import torch
+
+from workloads import LayerShape, make_workload
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run(entry, wl, init):
+    import paper_2411_19379_amd as ssm
+    s = wl.shape
+    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
+    y = torch.full_like(wl.inputs.x, float("nan"))
+    st = torch.full((max(wl.n_ckpt, 1), s.nheads, s.headdim, s.d_state), float("nan"), dtype=torch.float32, device=DEV)
+    ssm.prefill(plan, wl.inputs.x, wl.inputs.dt, wl.A, wl.inputs.B, wl.inputs.C, wl.D, init, y_out=y, state_out=st,
+                entry=entry)
+    torch.cuda.synchronize()
+    plan.close()
+    return y, st
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_noalloc_entry_matches_ssm_prefill(io):
+    import paper_2411_19379_amd as ssm
+    shape = LayerShape(4, 64, 128, 2, 256, io) if io == "bf16" else LayerShape(4, 16, 16, 1, 64, io)
+    big = make_workload(2, DEV, seed=301, batch=5, len_range=(1, 500), shape=shape)
+    small = make_workload(2, DEV, seed=302, batch=2, len_range=(1, 90), shape=shape)
+    for wl in (big, small):  # the second call is smaller: stale table entries of the first must not matter
+        print(f"noalloc {io}: {wl.batch} sequences, {wl.total_tokens} tokens", flush=True)
+        init = list(wl.init_state)
+        y_ref, st_ref = _run(ssm.ssm_prefill, wl, init)
+        y, st = _run(ssm.ssm_prefill_noalloc, wl, init)
+        # same kernels, same tables: bit-identical
+        bits = torch.int16 if io == "bf16" else torch.int32
+        assert torch.equal(y.view(bits), y_ref.view(bits))
+        assert torch.equal(st[: wl.n_ckpt].view(torch.int32), st_ref[: wl.n_ckpt].view(torch.int32))
+        assert not torch.isnan(y.float()).any() and not torch.isnan(st[: wl.n_ckpt]).any()
+
+
+def test_noalloc_rejects_oversized_plans():
+    import paper_2411_19379_amd as ssm
+    # one checkpoint per token makes one tile per token: 17000 tiles > 16384
+    T = 17000
+    plan = ssm.Plan(1, 16, 16, 1, 16, "f32", [0, T], [list(range(1, T + 1))])
+    with pytest.raises(ssm.SsmError) as e:
+        ssm.ssm_prefill_noalloc(plan.handle, 256, 256, 256, 256, 256, 256, None, 256, 256, None, 0, None)
+    assert e.value.code == ssm.SSM_ERR_UNSUPPORTED_SHAPE
+    plan.close()
