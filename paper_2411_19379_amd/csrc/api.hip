@@ -133,8 +133,6 @@ static int check_prefill(const ssm_plan *plan, const void *x, const void *dt, co
         return fail(SSM_ERR_INVALID_ARG, "a required tensor pointer is NULL");
     if (plan->n_ckpt > 0 && !state_out)
         return fail(SSM_ERR_INVALID_ARG, "state_out is NULL but the plan has checkpoints");
-    if (plan->path == SSM_PATH_MFMA_BF16 && plan->shape.state_dtype != SSM_ST_F32)
-        return fail(SSM_ERR_UNSUPPORTED_SHAPE, "the matrix-core scan keeps fp32 cached states only");
     const void *ptrs[] = {x, dt, A, B, C, D, y_out, state_out};
     for (const void *p : ptrs)
         if (!aligned16(p))

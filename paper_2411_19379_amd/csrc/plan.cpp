@@ -203,8 +203,12 @@ extern "C" int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes)
 {
     if (!plan || !bytes)
         return fail(SSM_ERR_INVALID_ARG, "plan or bytes is NULL");
-    // The scan carries every sequence's state in registers from its first to
-    // its last token, so no intermediate state goes through device memory.
-    *bytes = 0;
+    // The running state never leaves the chip between tiles; the matrix-core scan needs room for the operands
+    // that the heads of a group share (written by its first kernel, read by its second).
+    size_t n = 0;
+    if (plan->path == SSM_PATH_MFMA_BF16)
+        n = plan->tiles.size() * ((size_t)plan->shape.ngroups * kMfmaTileGroupBytes +
+                                  (size_t)plan->shape.nheads * kMfmaDtBytes);
+    *bytes = (n + 255) / 256 * 256;
     return SSM_OK;
 }

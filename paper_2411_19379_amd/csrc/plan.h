@@ -53,3 +53,8 @@ void ssm_set_error(const std::string &msg);
 // Tile lengths the two kernel families work with.
 constexpr int kValuTileTokens = 16;
 constexpr int kMfmaTileTokens = 64;
+
+// Workspace of the matrix-core scan: per (tile, group) the operands the heads of a group share (C and B^T as fp16
+// register images, 16 KiB each, and the raw score blocks, 6 KiB), then per (tile, head) the tile's dt, 64 bf16.
+constexpr size_t kMfmaTileGroupBytes = 38912;
+constexpr size_t kMfmaDtBytes = 128;

@@ -1,126 +1,143 @@
-// bf16 MFMA scan kernel for gfx950: d_state 128, headdim a multiple of 32,
-// bf16 x/dt/B/C/y, fp32 A/D/state.
+// Matrix-core scan for gfx950: d_state 128, headdim a multiple of 32, bf16 x/dt/B/C/y, fp32 A/D, cached states in
+// fp32, fp16 or bf16.
 //
-// One workgroup owns one (sequence, head, 32-channel slice) and walks the
-// sequence's tiles in order; the slice's [32,128] state stays in MFMA
-// accumulators from the first token to the last, so states reach device
-// memory only as requested checkpoints.  Per tile of q <= 64 tokens starting
-// after token s, with l_i = A * sum_{k<=i} dt_k inside the tile:
+// Per tile of q <= 64 tokens starting after token s, with l_i = A * sum_{k<=i} dt_k inside the tile:
 //
 //   Gm[i,j] = (C_i.B_j) e^{l_i-l_j} dt_j   for j <= i, else 0   (masked score)
 //   y_i     = e^{l_i} (S_s C_i) + sum_j Gm[i,j] x_j + D x_i
 //   S_e     = e^{l_q} S_s + sum_j (e^{l_q-l_j} dt_j x_j) B_j^T
 //
-// All contractions run on the matrix cores with bf16 operands and fp32
-// accumulation; bf16 rounding touches only MFMA operands (Gm with D added on
-// its diagonal, the decay-weighted x, the copy of S used for S.C).  Decay
-// exponents, accumulators and checkpoints are fp32.
+// Only the last line chains one tile to the next, and only through an element-wise update of S; everything else
+// of a tile (scores, Gm.x, the tile-local state sum_j (...) B_j^T) is independent of the tiles before it.
 //
-// The 8 waves of a workgroup are specialised and form a software pipeline
-// over tiles with ONE workgroup barrier per tile.  In pipeline step k:
+// Two kernels.
 //
-//   waves 4,5,7  loaders: write tile k+2 into LDS (B; C; dt prefix sums, the
-//                per-token factor tables, x raw and decay-weighted) from
-//                registers filled by coalesced global loads one step earlier
-//   wave  6      off-diagonal score block (queries 32..63, keys 0..31) of
-//                tile k+1, handed over through a per-lane LDS mailbox that
-//                already holds the consumer's MFMA operand
-//   waves 0,1    token half 0 / 1.  For tile k: S.C with the C fragments and
-//                Gm.x with the masked diagonal score block this wave kept in
-//                registers from the step before, y staged through LDS and
-//                stored with coalesced writes.  For tile k+1: C fragments from
-//                LDS, diagonal score block, masking.
-//   waves 2,3    tile k: state update for 64 state indices each, bf16 copy of
-//                the new state for tile k+1, checkpoint stores
+// ssm_prep_kernel, one workgroup per (tile, group): what the heads of a group share.  B and C of the tile are read
+// once with coalesced rows, converted bf16 -> fp16 (exact for normal values) and written back in the register image
+// of the matrix-core operands the scan needs (B^T for the state update, C for S.C), together with the raw score
+// blocks C_i.B_j and the tile's dt transposed to head-major.  The scan then loads every operand with fully
+// contiguous 1 KiB wave loads straight into registers: B and C never pass through its LDS.
 //
-// Every global access is laid out so that four neighbouring lanes touch one
-// 64-byte segment; MFMA operand layouts are produced from LDS, never from
-// global memory directly.
+// ssm_scan_mfma_kernel, one workgroup per (sequence, head, 32-channel slice).  The waves of a workgroup take the
+// sequence's tiles round-robin and each wave computes ALL of its tile: tables of decay factors, masked scores,
+// Gm.x, the tile-local state (16 MFMAs into 64 accumulator registers), S.C, y.  The running state S lives in LDS as
+// the register image of those accumulators; the wave whose turn it is reads it, adds its tile-local state
+// (S <- e^{l_q} S + local), writes it back and uses the value it read for S.C.  The tile routine is cut into 8
+// phases with a workgroup barrier after each, and wave w runs `kStagger * w` rounds behind wave 0, so that in every
+// round at most one wave is in each phase: the hand-off of S (phases 4 to 6, block by block of 32 state indices) is
+// ordered by the barriers alone, while 8/kStagger tiles are in flight per workgroup to hide latencies.
+//
+// Rounding: operands of the two long contractions (state update, S.C) are fp16 (11 bits: the decay-weighted x, the
+// copy of S, B and C), those of Gm.x are bf16 (x as stored, Gm rounded once); decay exponents, accumulators, the
+// carried state and checkpoints are fp32.
+#include <mutex>
 #include <type_traits>
 
 #include "device_utils.h"
 
+// Optional cycle-trace hooks for profiling builds; they expand to nothing here.
+#ifndef SSM_TRACE
+#define SSM_TRACE(slot)
+#define SSM_TRACE_DECL
+#define SSM_TRACE_FLUSH
+#endif
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kThreads = 512;             // 8 waves
 constexpr int kQ = kMfmaTileTokens;  // 64 tokens per tile
 constexpr int kN = 128;              // d_state
 constexpr int kPW = 32;              // channels per workgroup
-constexpr int LDB = kN + 16;         // row stride (elements) of the B and state tiles
-constexpr int LDX = kPW;             // row stride of the x tiles (unpadded on purpose)
-constexpr int LDY = kPW + 8;         // row stride of the y staging tiles
+#ifndef SSM_SCAN_WAVES
+#define SSM_SCAN_WAVES 4
+#endif
+constexpr int kWaves = SSM_SCAN_WAVES;   // waves per workgroup of the scan: 4 or 8
+constexpr int kThreads = 64 * kWaves;
+constexpr int kPhases = 8;               // barriers per tile routine
+constexpr int kStagger = kPhases / kWaves;  // rounds between the starts of two consecutive waves
+static_assert(kWaves == 4 || kWaves == 8, "the phase schedule is written for 4 or 8 waves");
+constexpr int LDX = kPW;             // row stride of the x tile (unpadded on purpose: transpose reads)
+constexpr int LDY = kPW + 8;         // row stride of the y staging tile
 constexpr float kLog2e = 1.4426950408889634f;
 
-// per-token factors of one tile
-struct Tables {
-    float ell2[kQ];    // l_i * log2(e)
-    float cj[kQ];      // l_j * log2(e) - log2(dt_j)
-    float ei[kQ];      // e^{l_i}
-    float ri[kQ / 2];  // i >= 32: e^{l_i - l_31}
-    float cf[kQ / 2];  // j <  32: e^{l_31 - l_j} dt_j
-};
+// Operand images of one (tile, group) in the workspace, in uint4 units of 64 lanes each.
+constexpr int kCfWords = 2 * 8 * 64;  // C:   [token half][k-step of 16 state indices][lane]
+constexpr int kBfWords = 4 * 4 * 64;  // B^T: [block of 32 state indices][k-step of 16 tokens][lane]
+constexpr int kCbWords = 3 * 2 * 64;  // raw score blocks: [block][half of the 16 accumulator elements][lane]
+static_assert((kCfWords + kBfWords + kCbWords) * 16 == kMfmaTileGroupBytes, "workspace layout");
 
-struct Lds {
-    bf16_t Bs[3][kQ][LDB];        // B tile, token major
-    bf16_t Cs[2][kQ][LDB];        // C tile, token major
-    bf16_t Xr[3][kQ][LDX];        // x as loaded, token major
-    bf16_t Xs[3][kQ][LDX];        // e^{l_q-l_j} dt_j x_j, token major
-    bf16_t Ss[2][kPW][LDB];       // bf16 copy of the running state, channel major
-    uint4 M10[2][64][2];          // off-diagonal score block as the consumer lane's two MFMA operands
-    bf16_t Ys[2][kQ / 2][LDY];    // y of one token half on its way to coalesced stores
-    Tables tab[3];
-};
-
-__device__ __forceinline__ bf16x8 lds_frag(const bf16_t *p)
-{
-    return *reinterpret_cast<const bf16x8 *>(p);
-}
-
-// LDS transpose read: the 16 lanes of a group pass the addresses of 4 rows x
-// (4 lanes x 4 elements); lane i of the group receives column i of that 4x16
-// block, i.e. 4 elements that sit in 4 consecutive rows.
-__device__ __forceinline__ s16x4 lds_tr4(const bf16_t *p)
+__device__ __forceinline__ s16x4 lds_tr4(const void *p)
 {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
 }
 
-// 8 k-values of a transposed operand: two groups of 4 consecutive rows of a token-major tile
-__device__ __forceinline__ bf16x8 lds_frag_tr(const bf16_t *p_lo, const bf16_t *p_hi)
+// 8 k-values of a transposed operand: two groups of 4 consecutive rows of a row-major tile of 16-bit elements.
+// The 16 lanes of a group pass the addresses of 4 rows x (4 lanes x 4 elements); lane i of the group receives
+// column i of that 4x16 block.
+__device__ __forceinline__ uint4 lds_frag_tr(const void *p_lo, const void *p_hi)
 {
     const s16x4 lo = lds_tr4(p_lo), hi = lds_tr4(p_hi);
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    return __builtin_bit_cast(uint4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
 {
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+__device__ __forceinline__ uint32_t pack2_f16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+__device__ __forceinline__ float f16_lo(uint32_t u) { return (float)__builtin_bit_cast(f16x2, u)[0]; }
+__device__ __forceinline__ float f16_hi(uint32_t u) { return (float)__builtin_bit_cast(f16x2, u)[1]; }
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also
-// wait for every outstanding global load, i.e. for the prefetches of later
-// tiles.  Global memory written by this kernel is never read back by it, so
-// LDS ordering is all the pipeline stages need.
+// Global loads of the scan.  They are issued phases ahead of their use; the scheduling fences at the phase ends keep
+// them where they are written.
+__device__ __forceinline__ uint4 load16_here(const void *p) { return *static_cast<const uint4 *>(p); }
+__device__ __forceinline__ uint32_t load4_here(const void *p) { return *static_cast<const uint32_t *>(p); }
+
+// Wait for this wave's own LDS traffic (LDS executes a wave's accesses in order).
+__device__ __forceinline__ void lds_wait()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads issued for later phases stay in flight.  Global
+// memory written by these kernels is never read back by the same launch.
 __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// End of a phase of the scan's tile routine: nothing is scheduled across it.
+__device__ __forceinline__ void phase_end()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 #define SSM_DPP(old, v, ctrl, row_mask, bound)                                                        \
     __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, (float)(old)),       \
                                                           __builtin_bit_cast(int, (float)(v)), (ctrl), \
                                                           (row_mask), 0xF, (bound)))
-// Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and the
-// two row broadcasts (no LDS round trips).
+// Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and the two row broadcasts.
 __device__ __forceinline__ float wave_inclusive_sum(float v)
 {
     v += SSM_DPP(0.f, v, 0x111, 0xF, true);   // row_shr:1
@@ -143,482 +160,601 @@ __device__ __forceinline__ f32x16 zero16()
     return z;
 }
 
-// What every role needs to know; all members are wave-uniform.
-struct Ctx {
-    const bf16_t *__restrict__ x;
-    const bf16_t *__restrict__ dt;
-    const bf16_t *__restrict__ Bg;
-    const bf16_t *__restrict__ Cg;
-    bf16_t *__restrict__ y;
-    float *__restrict__ state_out;
-    const SsmTile *__restrict__ tiles;
-    const float *init;  // this sequence's initial state or nullptr
-    int H, P, G, h, g, pbase;
-    int tile_begin, n_tiles;
-    float Ah, Dh;
-};
-
-// Descriptor of tile k of this sequence; indices past the end are clamped
-// (those descriptors are never used).  Uniform index, so a scalar load.
-__device__ __forceinline__ SsmTile tile_at(const Ctx &c, int k)
+__device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c)
 {
-    const int kk = k < c.n_tiles ? k : c.n_tiles - 1;
-    return c.tiles[__builtin_amdgcn_readfirstlane(c.tile_begin + kk)];
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0,
+                                                   0);
 }
 
-// The pipeline loop shared by all roles: steps s = -2 .. n_tiles-1, one
-// workgroup barrier after each.  Steps come in groups of three so that
-// everything indexed by a tile number modulo 3 (LDS buffers, register rings
-// of prefetched data) is addressed statically: in step s = 3m - 2 + u,
-// (s + 2) % 3 == u.
-template <typename F>
-__device__ __forceinline__ void pipe_loop(int n_tiles, F &&body)
+__device__ __forceinline__ f32x16 mfma_f16(uint4 a, uint4 b, f32x16 c)
 {
-    for (int s0 = -2; s0 < n_tiles; s0 += 3) {
-        if (s0 + 0 < n_tiles) {
-            body(s0 + 0, std::integral_constant<int, 0>{});
-            lds_barrier();
-        }
-        if (s0 + 1 < n_tiles) {
-            body(s0 + 1, std::integral_constant<int, 1>{});
-            lds_barrier();
-        }
-        if (s0 + 2 < n_tiles) {
-            body(s0 + 2, std::integral_constant<int, 2>{});
-            lds_barrier();
-        }
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                  0);
+}
+
+// Four neighbouring elements of a cached state (element index idx) in its storage type.
+__device__ __forceinline__ float4 load_state4(const void *base, size_t idx, int state_dtype)
+{
+    if (state_dtype == SSM_ST_F16) {
+        const f16x4 h = *reinterpret_cast<const f16x4 *>(static_cast<const _Float16 *>(base) + idx);
+        return make_float4((float)h[0], (float)h[1], (float)h[2], (float)h[3]);
+    }
+    if (state_dtype == SSM_ST_BF16) {
+        const uint2 u = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(base) + idx);
+        return make_float4(bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y));
+    }
+    return *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + idx);
+}
+
+__device__ __forceinline__ void store_state4(void *base, size_t idx, float4 v, int state_dtype)
+{
+    if (state_dtype == SSM_ST_F16) {
+        const f16x4 h = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+        *reinterpret_cast<f16x4 *>(static_cast<_Float16 *>(base) + idx) = h;
+    } else if (state_dtype == SSM_ST_BF16) {
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(base) + idx) =
+            make_uint2(pack2_bf16(v.x, v.y), pack2_bf16(v.z, v.w));
+    } else {
+        *reinterpret_cast<float4 *>(static_cast<float *>(base) + idx) = v;
     }
 }
 
-// Mask and decay a diagonal 32x32 score block held as Gm^T accumulators
-// (element r of lane (i = lane%32, q = lane/32) is row j = 8(r/4) + 4q + r%4),
-// add D on the diagonal, and pack it as the two bf16 operands of the Gm.x MFMAs.
-__device__ __forceinline__ void mask_diag(const f32x16 &acc, const Tables &tb, int off, int i, int q, float Dh,
-                                          uint4 &g0, uint4 &g1)
+// ================================================================ per-(tile, group) operands
+constexpr int kPrepThreads = 256;
+constexpr int LDPB = kN + 32;  // row stride (halves) of the B tile: transpose reads and 16-byte row reads
+constexpr int LDPC = kN + 8;   // row stride of the C tile: row reads only
+constexpr int kDtHeads = 64;   // heads per pass of the dt transposition
+
+struct PrepLds {
+    _Float16 Bs[kQ][LDPB];
+    _Float16 Cs[kQ][LDPC];
+    bf16_t dts[kDtHeads][kQ + 2];
+};
+
+// 8 bf16 -> 8 fp16 (exact for values whose exponent fp16 can hold)
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 v)
 {
-    const float ell2_i = tb.ell2[off + i];
+    return make_uint4(pack2_f16(bf16_lo(v.x), bf16_hi(v.x)), pack2_f16(bf16_lo(v.y), bf16_hi(v.y)),
+                      pack2_f16(bf16_lo(v.z), bf16_hi(v.z)), pack2_f16(bf16_lo(v.w), bf16_hi(v.w)));
+}
+
+__global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
+    const bf16_t *__restrict__ Bg, const bf16_t *__restrict__ Cg, const bf16_t *__restrict__ dt,
+    const SsmTile *__restrict__ tiles, uint4 *__restrict__ frags, bf16_t *__restrict__ dt_t, int H, int G, int n_tiles)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    PrepLds &L = *reinterpret_cast<PrepLds *>(lds_raw);
+    const int tile = blockIdx.x / G, g = blockIdx.x % G;
+    if (tile >= n_tiles)
+        return;
+    const SsmTile t = tiles[tile];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hg = H / G;  // heads of this group: g * hg .. g * hg + hg - 1
+
+    // B and C rows, 16 lanes per 256-byte row; rows past the end of a partial tile are zero
+    {
+        const int row_l = tid >> 4, col = 8 * (tid & 15);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int row = row_l + 16 * kk;
+            uint4 vb = make_uint4(0, 0, 0, 0), vc = vb;
+            if (row < t.len) {
+                const size_t off = (((size_t)t.tok0 + row) * G + g) * kN + col;
+                vb = *reinterpret_cast<const uint4 *>(Bg + off);
+                vc = *reinterpret_cast<const uint4 *>(Cg + off);
+            }
+            *reinterpret_cast<uint4 *>(&L.Bs[row][col]) = bf16x8_to_f16x8(vb);
+            *reinterpret_cast<uint4 *>(&L.Cs[row][col]) = bf16x8_to_f16x8(vc);
+        }
+    }
+    // dt of the tile, transposed to head-major rows of 64 tokens, kDtHeads heads at a time.  The barrier after the
+    // first pass's loads also publishes the B and C tiles.
+    for (int h0 = 0; h0 < hg; h0 += kDtHeads) {
+        const int nh = hg - h0 < kDtHeads ? hg - h0 : kDtHeads;
+        if (h0 > 0)
+            __syncthreads();  // the previous pass has been written out
+        for (int idx = tid; idx < kQ * nh; idx += kPrepThreads) {
+            const int tok = idx / nh, hh = idx % nh;
+            bf16_t v = 0;
+            if (tok < t.len)
+                v = dt[((size_t)t.tok0 + tok) * H + g * hg + h0 + hh];
+            L.dts[hh][tok] = v;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < kQ * nh; idx += kPrepThreads) {
+            const int hh = idx / kQ, tok = idx % kQ;
+            dt_t[((size_t)tile * H + g * hg + h0 + hh) * kQ + tok] = L.dts[hh][tok];
+        }
+    }
+
+    uint4 *out = frags + (size_t)blockIdx.x * (kCfWords + kBfWords + kCbWords);
+    const int i = lane & 31, q = lane >> 5;
+    // C operand of S.C: lane (token i of a half, q), k-step ks: state indices 16 ks + 8 (e/4) + 4 q + e%4, the order
+    // in which a lane holds a block of the state in its accumulators
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        const int idx = 4 * w + f, ih = idx >> 3, ks = idx & 7;
+        const _Float16 *row = &L.Cs[32 * ih + i][16 * ks + 4 * q];
+        const uint2 lo = *reinterpret_cast<const uint2 *>(row), hi = *reinterpret_cast<const uint2 *>(row + 8);
+        out[(ih * 8 + ks) * 64 + lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    // B^T operand of the state update: lane (state index n%32, q), k-step ks: tokens 16 ks + 8 q + e
+    {
+        const int g4 = lane >> 4;
+        const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
+        const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
+        const _Float16 *pb = &L.Bs[tr_row][32 * w + tr_col];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            out[kCfWords + (w * 4 + ks) * 64 + lane] = lds_frag_tr(pb + 16 * ks * LDPB, pb + (16 * ks + 4) * LDPB);
+    }
+    // raw score blocks Gm^T[j, i] = B_j . C_i: block 0 keys and queries 0..31, block 1 keys and queries 32..63,
+    // block 2 keys 0..31 and queries 32..63; kept as the 16 accumulator elements of every lane, in fp16
+    if (w < 3) {
+        const _Float16 *pb = &L.Bs[(w == 1 ? 32 : 0) + i][8 * q];
+        const _Float16 *pc = &L.Cs[(w == 0 ? 0 : 32) + i][8 * q];
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            acc = mfma_f16(*reinterpret_cast<const uint4 *>(pb + 16 * ks), *reinterpret_cast<const uint4 *>(pc + 16 * ks),
+                           acc);
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+            out[kCfWords + kBfWords + (w * 2 + hf) * 64 + lane] =
+                make_uint4(pack2_f16(acc[8 * hf + 0], acc[8 * hf + 1]), pack2_f16(acc[8 * hf + 2], acc[8 * hf + 3]),
+                           pack2_f16(acc[8 * hf + 4], acc[8 * hf + 5]), pack2_f16(acc[8 * hf + 6], acc[8 * hf + 7]));
+    }
+}
+
+// ================================================================ the scan
+struct WaveLds {               // private to one wave
+    bf16_t Xr[kQ][LDX];        // x of the tile as loaded, token major
+    bf16_t Ys[kQ][LDY];        // y of the tile on its way to coalesced stores
+    float ell2[kQ];            // l_i * log2(e)
+    float cj[kQ];              // l_j * log2(e) - log2(dt_j)
+    float ei[kQ];              // e^{l_i}
+    float wt[kQ];              // e^{l_q - l_j} dt_j: weight of token j in the state update
+    float ri[kQ];              // e^{l_i - l_31}
+    float cf[kQ];              // e^{l_31 - l_j} dt_j
+};
+
+struct Lds {
+    float4 S[4][4][64];        // the running state: accumulator image [block of 32 n][element group a][lane]
+    WaveLds wv[kWaves];
+};
+
+// The 16 raw scores of a lane (accumulator image of a 32x32 block of Gm^T, fp16) as floats.
+__device__ __forceinline__ void unpack_scores(const uint4 &raw0, const uint4 &raw1, float (&v)[16])
+{
+    const uint32_t rw[8] = {raw0.x, raw0.y, raw0.z, raw0.w, raw1.x, raw1.y, raw1.z, raw1.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        v[2 * e] = f16_lo(rw[e]);
+        v[2 * e + 1] = f16_hi(rw[e]);
+    }
+}
+
+__device__ __forceinline__ void pack_scores(const float (&v)[16], uint4 &g0, uint4 &g1)
+{
+    g0 = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
+    g1 = make_uint4(pack2_bf16(v[8], v[9]), pack2_bf16(v[10], v[11]), pack2_bf16(v[12], v[13]), pack2_bf16(v[14], v[15]));
+}
+
+// Mask and decay a diagonal 32x32 block of raw scores held as the accumulator image of Gm^T (element r of lane
+// (i = lane%32, q = lane/32) is key j = 8(r/4) + 4q + r%4), add D on the diagonal, and pack it as the two bf16
+// operands of the Gm.x MFMAs.
+//   FAST: e^{l_i-l_j} dt_j = e^{l_i-l_31} * e^{l_31-l_j} dt_j from the two factor tables; the caller has checked that
+//         the decay over the whole tile stays inside the fp32 exponent range, so neither factor over- or underflows.
+//   else: one exponential of l_i - l_j per entry; no factor can overflow whatever the decay.
+template <bool FAST>
+__device__ __forceinline__ void mask_diag(const uint4 &raw0, const uint4 &raw1, const WaveLds &tb, int off, int i, int q,
+                                          float Dh, uint4 &g0, uint4 &g1)
+{
     float v[16];
+    unpack_scores(raw0, raw1, v);
+    const float fi = FAST ? tb.ri[off + i] : tb.ell2[off + i];
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-        const float4 c4 = *reinterpret_cast<const float4 *>(&tb.cj[off + 8 * a + 4 * q]);
+        const float4 c4 = *reinterpret_cast<const float4 *>(FAST ? &tb.cf[off + 8 * a + 4 * q] : &tb.cj[off + 8 * a + 4 * q]);
         const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int jl = 8 * a + 4 * q + r;
-            float g = jl <= i ? acc[4 * a + r] * exp2_fast(ell2_i - cc[r]) : 0.f;
-            if (jl == i)
-                g += Dh;
-            v[4 * a + r] = g;
+            const float f = FAST ? fi * cc[r] : exp2_fast(fi - cc[r]);
+            float gv = __builtin_fmaf(v[4 * a + r], f, jl == i ? Dh : 0.f);
+            v[4 * a + r] = jl <= i ? gv : 0.f;
         }
     }
-    g0 = make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-    g1 = make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
+    pack_scores(v, g0, g1);
 }
 
-// ---------------------------------------------------------------- loaders
-// One 64 x 128 bf16 tile (B or C) per step: 16 coalesced 16-byte loads per
-// lane (16 lanes per token row), written to LDS one step after they were
-// issued and two tiles ahead of the consumers.
-template <bool IS_C>
-__device__ __forceinline__ void role_load_bc(const Ctx &c, Lds &L, int lane)
-{
-    uint4 r[16];
-    const bf16_t *src = IS_C ? c.Cg : c.Bg;
-    const int row_l = lane >> 4, col = 8 * (lane & 15);
-    auto issue = [&](const SsmTile &t) {
-        const bf16_t *p = src + (((size_t)t.tok0 + row_l) * c.G + c.g) * kN + col;
-        const size_t step = (size_t)4 * c.G * kN;
-        if (t.len == kQ) {  // full tile: no predication
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk)
-                r[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                r[kk] = make_uint4(0, 0, 0, 0);
-                if (row_l + 4 * kk < t.len)
-                    r[kk] = *reinterpret_cast<const uint4 *>(p + kk * step);
-            }
-        }
-    };
-    issue(tile_at(c, 0));
-    SsmTile dpf = tile_at(c, 1);
-    pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;  // == (s + 2) % 3: LDS buffer of tile k in a ring of three
-        const int k = s + 2;
-        if (k < c.n_tiles) {
-            bf16_t(*dst)[LDB] = IS_C ? L.Cs[k & 1] : L.Bs[u];
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk)
-                *reinterpret_cast<uint4 *>(&dst[row_l + 4 * kk][col]) = r[kk];
-            if (k + 1 < c.n_tiles)
-                issue(dpf);
-            dpf = tile_at(c, k + 2);
-        }
-    });
-}
-
-// dt prefix sums, the per-token factor tables and the two x tiles.
-__device__ __forceinline__ void role_load_x(const Ctx &c, Lds &L, int lane)
-{
-    uint32_t dt_raw = 0;
-    uint4 xr[4];
-    auto issue = [&](const SsmTile &t) {
-        const bf16_t *px = c.x + (((size_t)t.tok0 + (lane >> 2)) * c.H + c.h) * c.P + c.pbase + 8 * (lane & 3);
-        const size_t xstep = (size_t)16 * c.H * c.P;
-        dt_raw = 0;
-        if (lane < t.len)
-            dt_raw = c.dt[((size_t)t.tok0 + lane) * c.H + c.h];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            xr[kk] = make_uint4(0, 0, 0, 0);
-            if ((lane >> 2) + 16 * kk < t.len)
-                xr[kk] = *reinterpret_cast<const uint4 *>(px + kk * xstep);
-        }
-    };
-    issue(tile_at(c, 0));
-    SsmTile dpf = tile_at(c, 1);
-    pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;  // == (s + 2) % 3
-        const int k = s + 2;
-        if (k < c.n_tiles) {
-            Tables &tb = L.tab[u];
-            const float dtj = __uint_as_float(dt_raw << 16);
-            const float ell2 = wave_inclusive_sum(dtj * c.Ah) * kLog2e;
-            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
-            const float wj = exp2_fast(last - ell2) * dtj;  // weight of token `lane` in the state update
-            tb.ell2[lane] = ell2;
-            tb.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
-            tb.ei[lane] = exp2_fast(ell2);
-            if (lane >= 32)
-                tb.ri[lane - 32] = exp2_fast(ell2 - e31);
-            else
-                tb.cf[lane] = exp2_fast(e31 - ell2) * dtj;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int tok = (lane >> 2) + 16 * kk;
-                const float wt = __shfl(wj, tok, 64);
-                const uint4 xq = xr[kk];
-                *reinterpret_cast<uint4 *>(&L.Xr[u][tok][8 * (lane & 3)]) = xq;
-                const uint32_t xv[4] = {xq.x, xq.y, xq.z, xq.w};
-                uint32_t o[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    o[e] = pack2(wt * __uint_as_float(xv[e] << 16), wt * __uint_as_float(xv[e] & 0xffff0000u));
-                *reinterpret_cast<uint4 *>(&L.Xs[u][tok][8 * (lane & 3)]) = make_uint4(o[0], o[1], o[2], o[3]);
-            }
-            if (k + 1 < c.n_tiles)
-                issue(dpf);
-            dpf = tile_at(c, k + 2);
-        }
-    });
-}
-
-// ---------------------------------------------------------------- off-diagonal scores of tile k+1
-// Gm^T[j, i] for keys j in 0..31 and queries i in 32..63: every entry is
-// unmasked and the decay factorises as e^{l_i-l_31} * e^{l_31-l_j} dt_j, both
-// factors <= 1.  Accumulator element r of lane (i = lane%32, q = lane/32) is key
-// j = 8(r/4) + 4q + r%4; the consumer's MFMA takes exactly these values as its
-// operand when its other operand lists tokens in the same order, so the packed
-// block is mailed lane to lane.
-__device__ __forceinline__ void role_offdiag(const Ctx &c, Lds &L, int lane)
-{
-    const int i = lane & 31, q = lane >> 5;
-    pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;
-        constexpr int b = (u + 2) % 3;  // == (s + 1) % 3
-        const int k = s + 1;
-        if (k >= 0 && k < c.n_tiles) {
-            const Tables &tb = L.tab[b];
-            const bf16_t *pa = &L.Bs[b][i][8 * q];
-            const bf16_t *pc = &L.Cs[k & 1][32 + i][8 * q];
-            bf16x8 fa[8], fc[8];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                fa[ks] = lds_frag(pa + 16 * ks);
-                fc[ks] = lds_frag(pc + 16 * ks);
-            }
-            const float ri = tb.ri[i];
-            float4 c4[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                c4[a] = *reinterpret_cast<const float4 *>(&tb.cf[8 * a + 4 * q]);
-            f32x16 acc = zero16();
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fc[ks], acc, 0, 0, 0);
-            float v[16];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                v[4 * a + 0] = acc[4 * a + 0] * (ri * c4[a].x);
-                v[4 * a + 1] = acc[4 * a + 1] * (ri * c4[a].y);
-                v[4 * a + 2] = acc[4 * a + 2] * (ri * c4[a].z);
-                v[4 * a + 3] = acc[4 * a + 3] * (ri * c4[a].w);
-            }
-            L.M10[k & 1][lane][0] =
-                make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-            L.M10[k & 1][lane][1] =
-                make_uint4(pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
-        }
-    });
-}
-
-// ---------------------------------------------------------------- token half IH: outputs of tile k, scores of tile k+1
-template <int IH>
-__device__ __forceinline__ void role_half(const Ctx &c, Lds &L, int lane)
-{
-    const int i = lane & 31, q = lane >> 5;
-    // transpose-read addressing: lane group g4 = lane/16 covers channel block
-    // g4&1; tokens come in the order 8(e/4) + 4q + e%4, as in the scores
-    const int g4 = lane >> 4;
-    const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-    const int tr_row = 4 * (g4 >> 1) + ((lane & 15) >> 2);
-    // carried from the scores part of one step to the outputs part of the next
-    bf16x8 cf[8];       // C fragments of this half
-    uint4 g0, g1;       // masked diagonal score block as two MFMA operands
-    g0 = g1 = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-        cf[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-    pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;
-        constexpr int b = (u + 1) % 3;   // == s % 3 for s >= 0
-        constexpr int bn = (u + 2) % 3;  // == (s + 1) % 3
-        // ---- LDS reads of both parts, issued before anything waits for them ----
-        bf16x8 fs[8], x0, x1, x2, x3;
-        uint4 m0, m1;
-        float ei = 0.f;
-        if (s >= 0) {
-            const bf16_t *ps = &L.Ss[(s + 1) & 1][i][8 * q];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                fs[ks] = lds_frag(ps + 16 * ks);
-            const bf16_t *px = &L.Xr[b][32 * IH + tr_row][tr_col];
-            x0 = lds_frag_tr(px, px + 8 * LDX);
-            x1 = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
-            if (IH == 1) {
-                const bf16_t *px0 = &L.Xr[b][tr_row][tr_col];
-                x2 = lds_frag_tr(px0, px0 + 8 * LDX);
-                x3 = lds_frag_tr(px0 + 16 * LDX, px0 + 24 * LDX);
-                m0 = L.M10[s & 1][lane][0];
-                m1 = L.M10[s & 1][lane][1];
-            }
-            ei = L.tab[b].ei[32 * IH + i];
-        }
-        bf16x8 cn[8], fb[8];
-        const bool have_next = s + 1 < c.n_tiles;
-        if (have_next) {
-            const bf16_t *pc = &L.Cs[(s + 1) & 1][32 * IH + i][8 * q];
-            const bf16_t *pb = &L.Bs[bn][32 * IH + i][8 * q];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                cn[ks] = lds_frag(pc + 16 * ks);
-                fb[ks] = lds_frag(pb + 16 * ks);
-            }
-        }
-        // Two independent MFMA chains back to back: first the diagonal score
-        // block of tile s+1, then S.C of tile s.  The vector-ALU masking of the
-        // first overlaps the matrix work of the second.
-        f32x16 acc = zero16(), Y = zero16();
-        if (have_next) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], cn[ks], acc, 0, 0, 0);
-        }
-        if (s >= 0) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs[ks], cf[ks], Y, 0, 0, 0);
-        }
-        uint4 gn0 = make_uint4(0, 0, 0, 0), gn1 = gn0;
-        if (have_next)
-            mask_diag(acc, L.tab[bn], 32 * IH, i, q, c.Dh, gn0, gn1);
-        // ---- outputs of tile s ----
-        if (s >= 0) {
-            const SsmTile t = tile_at(c, s);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                Y[r] *= ei;
-            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, __builtin_bit_cast(bf16x8, g0), Y, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, __builtin_bit_cast(bf16x8, g1), Y, 0, 0, 0);
-            if (IH == 1) {
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2, __builtin_bit_cast(bf16x8, m0), Y, 0, 0, 0);
-                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x3, __builtin_bit_cast(bf16x8, m1), Y, 0, 0, 0);
-            }
-            // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of
-            // token i.  Through this wave's own LDS tile to token-major rows, then
-            // 16 bytes per lane with four lanes per 64-byte row of y.
-            bf16_t(*ys)[LDY] = L.Ys[IH];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                *reinterpret_cast<uint2 *>(&ys[i][8 * a + 4 * q]) =
-                    make_uint2(pack2(Y[4 * a], Y[4 * a + 1]), pack2(Y[4 * a + 2], Y[4 * a + 3]));
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // same wave: LDS executes in order
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const int tok = (lane >> 2) + 16 * m;
-                const uint4 o = *reinterpret_cast<const uint4 *>(&ys[tok][8 * (lane & 3)]);
-                if (32 * IH + tok < t.len)
-                    *reinterpret_cast<uint4 *>(c.y + (((size_t)t.tok0 + 32 * IH + tok) * c.H + c.h) * c.P + c.pbase +
-                                               8 * (lane & 3)) = o;
-            }
-        }
-        // the scores part hands its C fragments and masked block to the next step
-        if (have_next) {
-            g0 = gn0;
-            g1 = gn1;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                cf[ks] = cn[ks];
-        }
-    });
-}
-
-// ---------------------------------------------------------------- state update of tile k, 64 state indices
-__device__ __forceinline__ void role_state(const Ctx &c, Lds &L, int lane, int sw)
-{
-    // S^T tiles: rows n = 64sw + 32t + 8(r/4) + 4(lane/32) + r%4, column p = lane%32
-    const int p = lane & 31, q = lane >> 5;
-    f32x16 S[2];
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int n0 = 64 * sw + 32 * t2 + 8 * a + 4 * q;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c.init)
-                v = *reinterpret_cast<const float4 *>(c.init + ((size_t)c.h * c.P + c.pbase + p) * kN + n0);
-            S[t2][4 * a + 0] = v.x;
-            S[t2][4 * a + 1] = v.y;
-            S[t2][4 * a + 2] = v.z;
-            S[t2][4 * a + 3] = v.w;
-            *reinterpret_cast<uint2 *>(&L.Ss[1][p][n0]) = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
-        }
-    // transpose reads, natural token order: group g4 covers row/column block
-    // g4&1 and tokens 8(g4>>1) + 0..7 of each 16-token k-step
-    const int g4 = lane >> 4;
-    const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
-    const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-    pipe_loop(c.n_tiles, [&](int s, auto U) {
-        constexpr int u = decltype(U)::value;
-        constexpr int b = (u + 1) % 3;  // == s % 3 for s >= 0
-        if (s >= 0) {
-            const SsmTile t = tile_at(c, s);
-            const float dl = L.tab[b].ei[kQ - 1];  // padded tokens have dt = 0, so this is e^{l_len}
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                S[0][r] *= dl;
-                S[1][r] *= dl;
-            }
-            const bf16_t *pb = &L.Bs[b][tr_row][64 * sw + tr_col];
-            const bf16_t *px = &L.Xs[b][tr_row][tr_col];
-            bf16x8 fx[4], f0[4], f1[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                fx[ks] = lds_frag_tr(px + 16 * ks * LDX, px + (16 * ks + 4) * LDX);
-                f0[ks] = lds_frag_tr(pb + 16 * ks * LDB, pb + (16 * ks + 4) * LDB);
-                f1[ks] = lds_frag_tr(pb + 16 * ks * LDB + 32, pb + (16 * ks + 4) * LDB + 32);
-            }
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[ks], fx[ks], S[0], 0, 0, 0);
-                S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks], fx[ks], S[1], 0, 0, 0);
-            }
-            // bf16 copy for the next tile's S.C product; checkpoint
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const int n0 = 64 * sw + 32 * t2 + 8 * a + 4 * q;
-                    *reinterpret_cast<uint2 *>(&L.Ss[s & 1][p][n0]) =
-                        make_uint2(pack2(S[t2][4 * a], S[t2][4 * a + 1]), pack2(S[t2][4 * a + 2], S[t2][4 * a + 3]));
-                    if (t.ckpt_slot >= 0)
-                        *reinterpret_cast<float4 *>(c.state_out +
-                                                    (((size_t)t.ckpt_slot * c.H + c.h) * c.P + c.pbase + p) * kN + n0) =
-                            make_float4(S[t2][4 * a], S[t2][4 * a + 1], S[t2][4 * a + 2], S[t2][4 * a + 3]);
-                }
-        }
-    });
-}
-
-// Pointers are separate __restrict__ parameters (not a struct) so that the
-// compiler may read the read-only tables with scalar loads.
+// ST: storage type of cached states (ssm_state_dtype_t).
+template <int ST>
 __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
-    const bf16_t *__restrict__ x, const bf16_t *__restrict__ dt, const float *__restrict__ A_,
-    const bf16_t *__restrict__ Bg, const bf16_t *__restrict__ Cg, const float *__restrict__ D_,
-    bf16_t *__restrict__ y, float *__restrict__ state_out, const float *const *__restrict__ init_ptrs,
-    const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P, int G, int p_split,
-    int wg_per_xcd, int n_wg)
+    const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
+    void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
+    const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
+    int G, int p_split, int wg_per_xcd, int n_wg)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     Lds &L = *reinterpret_cast<Lds *>(lds_raw);
 
-    // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that
-    // consecutive logical ids (same head, then same group) share an XCD's L2.
+    // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical ids (same head,
+    // then same group) share an XCD's L2.
     const int wg = (blockIdx.x & 7) * wg_per_xcd + (blockIdx.x >> 3);
     if (wg >= n_wg)
         return;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    Ctx c;
-    c.x = x;
-    c.dt = dt;
-    c.Bg = Bg;
-    c.Cg = Cg;
-    c.y = y;
-    c.state_out = state_out;
-    c.tiles = tiles;
-    c.H = H;
-    c.P = P;
-    c.G = G;
     const int ps = wg % p_split;
-    c.h = (wg / p_split) % H;
+    const int h = (wg / p_split) % H;
     const int seq = wg / (p_split * H);
-    c.g = c.h / (H / G);
-    c.pbase = ps * kPW;
-    c.Ah = A_[c.h];
-    c.Dh = D_[c.h];
-    c.init = init_ptrs ? init_ptrs[seq] : nullptr;
+    const int g = h / (H / G);
+    const int pbase = ps * kPW;
+    const float Ah = A_[h], Dh = D_[h];
+    const void *init = init_ptrs ? init_ptrs[seq] : nullptr;
     const SsmSeq sq = seqs[seq];
-    c.tile_begin = sq.tile_begin;
-    c.n_tiles = sq.tile_end - sq.tile_begin;
-    if (c.n_tiles <= 0)
+    const int tile_begin = sq.tile_begin;
+    const int n_tiles = sq.tile_end - sq.tile_begin;
+    if (n_tiles <= 0)
         return;  // empty sequence: the whole workgroup leaves before any barrier
 
-    // Every role runs the same number of barriers: n_tiles + 2 pipeline steps.
-    switch (w) {
-    case 0: role_half<0>(c, L, lane); break;
-    case 1: role_half<1>(c, L, lane); break;
-    case 2: role_state(c, L, lane, 0); break;
-    case 3: role_state(c, L, lane, 1); break;
-    case 4: role_load_bc<false>(c, L, lane); break;
-    case 5: role_load_bc<true>(c, L, lane); break;
-    case 6: role_offdiag(c, L, lane); break;
-    default: role_load_x(c, L, lane); break;
+    WaveLds &W = L.wv[w];
+    const int i = lane & 31, q = lane >> 5;
+    const int g4 = lane >> 4;
+    const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
+    const int tr_row_nat = 8 * (g4 >> 1) + ((lane & 15) >> 2);  // tokens 16 ks + 8 q + e (state update)
+    const int tr_row_sc = 4 * (g4 >> 1) + ((lane & 15) >> 2);   // tokens 8 (e/4) + 4 q + e%4 (score order)
+    const int tok_l = lane >> 2, xcol = 8 * (lane & 3);
+    const size_t state_row = ((size_t)h * P + pbase + i) * kN + 4 * q;  // + 32 nb + 8 a: this lane's 4 state values
+    const size_t xrow = (size_t)H * P;                                   // elements per token row of x and y
+    const size_t xlane = (size_t)h * P + pbase + xcol;
+    // Warm-up of L2 for the wave's next tile: the workgroups of a group share the group's operand images, so each of
+    // them touches its share of the images' 128-byte lines (one 4-byte load per line), all 64 of its own x rows and
+    // the line of its dt.  The values only feed `touched`, which nothing reads back.
+    const int wg_in_group = (h % (H / G)) * p_split + ps, wgs_per_group = (H / G) * p_split;
+    constexpr int kImageLines = (int)(kMfmaTileGroupBytes / 128);
+    const int lines_per_wg = (kImageLines + wgs_per_group - 1) / wgs_per_group;
+    const int my_line = wg_in_group * lines_per_wg + lane;  // valid if lane < lines_per_wg and my_line < kImageLines
+    uint32_t touched = 0, touch0 = 0, touch1 = 0, touch2 = 0;
+
+    // Every wave runs the same number of barriers: kStagger * w rounds of delay, n_iter tile routines of kPhases
+    // barriers (tiles k = it * kWaves + w; past the end of the sequence the routine is barriers only), and the
+    // rounds by which the later waves lag behind.
+    const int n_iter = (n_tiles + kWaves - 1) / kWaves;
+    // The state the sequence starts from (its cached state or zero) goes into LDS the way a tile would have left it.
+    for (int blk = w; blk < 16; blk += kWaves) {
+        const int nb = blk >> 2, a = blk & 3;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (init)
+            v = load_state4(init, state_row + 32 * nb + 8 * a, ST);
+        L.S[nb][a][lane] = v;
     }
+    lds_barrier();
+    for (int b = 0; b < kStagger * w; ++b)
+        lds_barrier();
+    SSM_TRACE_DECL
+    SsmTile t_next = tiles[__builtin_amdgcn_readfirstlane(tile_begin + (w < n_tiles ? w : 0))];
+    for (int it = 0; it < n_iter; ++it) {
+        const int k = it * kWaves + w;
+        if (k >= n_tiles) {
+#pragma unroll
+            for (int b = 0; b < kPhases; ++b)
+                lds_barrier();
+            continue;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int tile_idx = __builtin_amdgcn_readfirstlane(tile_begin + k);
+        const SsmTile t = t_next;  // read while the previous tile of this wave was in its phase 4
+        const uint4 *fr = frags + ((size_t)tile_idx * G + g) * (kCfWords + kBfWords + kCbWords) + lane;
+        SSM_TRACE(8);
+
+        // ---------------- phase 0: this tile's loads of dt, x, the raw scores and the B^T operand.  Rows past the
+        // end of a partial tile re-read the tile's last row: their weights are zero, so any finite value will do.
+        touched ^= touch0 ^ touch1 ^ touch2;  // the warm-up loads of the previous tile have long arrived
+        const uint32_t dt_raw = dt_t[((size_t)tile_idx * H + h) * kQ + lane];
+        uint4 xr[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int tok = tok_l + 16 * kk < t.len ? tok_l + 16 * kk : t.len - 1;
+            xr[kk] = load16_here(x + ((size_t)t.tok0 + tok) * xrow + xlane);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // dt and x first: the next phase waits for them, not for what follows
+        uint4 cb[3][2];
+#pragma unroll
+        for (int blk = 0; blk < 3; ++blk)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                cb[blk][hf] = load16_here(fr + kCfWords + kBfWords + (blk * 2 + hf) * 64);
+        uint4 bf[4][4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                bf[nb][ks] = load16_here(fr + kCfWords + (nb * 4 + ks) * 64);
+        SSM_TRACE(0);
+        phase_end();
+        SSM_TRACE(15);
+
+        // ---------------- phase 1: factor tables, x into LDS, decay-weighted x as the fp16 operand
+        float dl;
+        bool fast;
+        {
+            const float dtj = __uint_as_float(dt_raw << 16);
+            const float ell2 = wave_inclusive_sum(dtj * Ah) * kLog2e;
+            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
+            dl = exp2_fast(last);   // padded tokens have dt = 0, so this is e^{l_len}
+            fast = last > -100.f;   // 2^+-100 is far inside the fp32 range: the two-factor form of the decay is safe
+            W.ell2[lane] = ell2;
+            W.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
+            W.ei[lane] = exp2_fast(ell2);
+            W.wt[lane] = exp2_fast(last - ell2) * dtj;
+            W.ri[lane] = exp2_fast(ell2 - e31);
+            W.cf[lane] = exp2_fast(e31 - ell2) * dtj;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                *reinterpret_cast<uint4 *>(&W.Xr[tok_l + 16 * kk][xcol]) = xr[kk];
+        }
+        lds_wait();
+        uint4 xw[4];
+        {
+            const bf16_t *px = &W.Xr[tr_row_nat][tr_col];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const uint4 xv = lds_frag_tr(px + 16 * ks * LDX, px + (16 * ks + 4) * LDX);
+                const float4 w0 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q]);
+                const float4 w1 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q + 4]);
+                xw[ks] = make_uint4(pack2_f16(w0.x * bf16_lo(xv.x), w0.y * bf16_hi(xv.x)),
+                                    pack2_f16(w0.z * bf16_lo(xv.y), w0.w * bf16_hi(xv.y)),
+                                    pack2_f16(w1.x * bf16_lo(xv.z), w1.y * bf16_hi(xv.z)),
+                                    pack2_f16(w1.z * bf16_lo(xv.w), w1.w * bf16_hi(xv.w)));
+            }
+        }
+        SSM_TRACE(1);
+        phase_end();
+        SSM_TRACE(15);
+
+        // ---------------- phase 2: tile-local state sum_j (e^{l_q-l_j} dt_j x_j) B_j^T on the matrix cores; under
+        // it, the loads of C for the first half of the state indices and the masked scores of the first token half
+        f32x16 Sl[4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+            Sl[nb] = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+                Sl[nb] = mfma_f16(bf[nb][ks], xw[ks], Sl[nb]);
+        uint4 cfr[2][2][4];  // [half of the state indices][token half][k-step]
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                cfr[0][ih][ks] = load16_here(fr + (ih * 8 + ks) * 64);
+        uint4 gd[2][2], go[2];
+        if (fast)
+            mask_diag<true>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
+        else
+            mask_diag<false>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
+        SSM_TRACE(2);
+        phase_end();
+        SSM_TRACE(15);
+
+        // ---------------- phase 3: the other score blocks, x in score order, intra-tile term Gm.x (+ D x on the
+        // diagonal)
+        if (fast)
+            mask_diag<true>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
+        else
+            mask_diag<false>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
+        {
+            // off-diagonal block (keys 0..31, queries 32..63): unmasked, and both factors of
+            // e^{l_i-l_31} * e^{l_31-l_j} dt_j are <= 1 whatever the decay
+            float v[16];
+            unpack_scores(cb[2][0], cb[2][1], v);
+            const float ri = W.ri[32 + i];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const float4 f4 = *reinterpret_cast<const float4 *>(&W.cf[8 * a + 4 * q]);
+                v[4 * a + 0] *= ri * f4.x;
+                v[4 * a + 1] *= ri * f4.y;
+                v[4 * a + 2] *= ri * f4.z;
+                v[4 * a + 3] *= ri * f4.w;
+            }
+            pack_scores(v, go[0], go[1]);
+        }
+        f32x16 Yi[2];
+        {
+            uint4 xs[2][2];  // x^T of each token half, tokens in the order of the score blocks' rows
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih) {
+                const bf16_t *px = &W.Xr[32 * ih + tr_row_sc][tr_col];
+                xs[ih][0] = lds_frag_tr(px, px + 8 * LDX);
+                xs[ih][1] = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
+            }
+            Yi[0] = mfma_bf16(xs[0][0], gd[0][0], zero16());
+            Yi[1] = mfma_bf16(xs[1][0], gd[1][0], zero16());
+            Yi[0] = mfma_bf16(xs[0][1], gd[0][1], Yi[0]);
+            Yi[1] = mfma_bf16(xs[1][1], gd[1][1], Yi[1]);
+            Yi[1] = mfma_bf16(xs[0][0], go[0], Yi[1]);
+            Yi[1] = mfma_bf16(xs[0][1], go[1], Yi[1]);
+        }
+        SSM_TRACE(3);
+        phase_end();
+        SSM_TRACE(15);
+
+        // ---------------- phases 4 to 6: the state hand-off, block by block of 32 state indices (block 0 in phase 4,
+        // blocks 1 and 2 in phase 5, block 3 in phase 6).  S as it was before this tile comes from LDS, where the
+        // wave of the previous tile left that block one round ago; this tile's S goes back in its place.  The value
+        // read also feeds S.C.
+        f32x16 Yo[2];
+        Yo[0] = zero16();
+        Yo[1] = zero16();
+        auto hand_off = [&](int nb, const float4(&sp)[4]) {
+            float4 sn[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                sn[a] = make_float4(__builtin_fmaf(dl, sp[a].x, Sl[nb][4 * a + 0]), __builtin_fmaf(dl, sp[a].y, Sl[nb][4 * a + 1]),
+                                    __builtin_fmaf(dl, sp[a].z, Sl[nb][4 * a + 2]), __builtin_fmaf(dl, sp[a].w, Sl[nb][4 * a + 3]));
+                L.S[nb][a][lane] = sn[a];
+            }
+            if (t.ckpt_slot >= 0) {
+                const size_t slot_row = (size_t)t.ckpt_slot * H * P * kN + state_row + 32 * nb;
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    store_state4(state_out, slot_row + 8 * a, sn[a], ST);
+            }
+            // S_s C_i over the 32 state indices of this block: two k-steps of 16
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint4 s16 = make_uint4(pack2_f16(sp[2 * hf].x, sp[2 * hf].y), pack2_f16(sp[2 * hf].z, sp[2 * hf].w),
+                                             pack2_f16(sp[2 * hf + 1].x, sp[2 * hf + 1].y),
+                                             pack2_f16(sp[2 * hf + 1].z, sp[2 * hf + 1].w));
+                Yo[0] = mfma_f16(s16, cfr[nb >> 1][0][2 * (nb & 1) + hf], Yo[0]);
+                Yo[1] = mfma_f16(s16, cfr[nb >> 1][1][2 * (nb & 1) + hf], Yo[1]);
+            }
+        };
+        {   // phase 4
+            float4 sp[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                sp[a] = L.S[0][a][lane];
+            // C for the other half of the state indices arrives during the next phase
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    cfr[1][ih][ks] = load16_here(fr + (ih * 8 + 4 + ks) * 64);
+            if (k + kWaves < n_tiles) {  // touch what this wave's next tile will load, four rounds from now
+                const int nxt = __builtin_amdgcn_readfirstlane(tile_idx + kWaves);
+                t_next = tiles[nxt];
+                const uint32_t *img = reinterpret_cast<const uint32_t *>(
+                    frags + ((size_t)nxt * G + g) * (kCfWords + kBfWords + kCbWords));
+                if (lane < lines_per_wg && my_line < kImageLines)
+                    touch0 = load4_here(img + my_line * 32);
+                if (lane < t_next.len)
+                    touch1 = load4_here(x + ((size_t)t_next.tok0 + lane) * xrow + (size_t)h * P + pbase);
+                if (lane == 63)
+                    touch2 = load4_here(dt_t + ((size_t)nxt * H + h) * kQ);
+            }
+            hand_off(0, sp);
+        }
+        SSM_TRACE(4);
+        phase_end();
+        SSM_TRACE(15);
+        {   // phase 5
+            float4 sp1[4], sp2[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                sp1[a] = L.S[1][a][lane];
+                sp2[a] = L.S[2][a][lane];
+            }
+            hand_off(1, sp1);
+            hand_off(2, sp2);
+        }
+        SSM_TRACE(5);
+        phase_end();
+        SSM_TRACE(15);
+        {   // phase 6, and y = e^{l_i} (S C_i) + intra-tile term on its way to LDS
+            float4 sp[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                sp[a] = L.S[3][a][lane];
+            hand_off(3, sp);
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih) {
+                const float ei = W.ei[32 * ih + i];
+                // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of token 32 ih + i
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float v0 = __builtin_fmaf(ei, Yo[ih][4 * a + 0], Yi[ih][4 * a + 0]);
+                    const float v1 = __builtin_fmaf(ei, Yo[ih][4 * a + 1], Yi[ih][4 * a + 1]);
+                    const float v2 = __builtin_fmaf(ei, Yo[ih][4 * a + 2], Yi[ih][4 * a + 2]);
+                    const float v3 = __builtin_fmaf(ei, Yo[ih][4 * a + 3], Yi[ih][4 * a + 3]);
+                    *reinterpret_cast<uint2 *>(&W.Ys[32 * ih + i][8 * a + 4 * q]) = make_uint2(pack2_bf16(v0, v1), pack2_bf16(v2, v3));
+                }
+            }
+        }
+        SSM_TRACE(6);
+        phase_end();
+        SSM_TRACE(15);
+
+        // ---------------- phase 7: y from LDS to device memory in coalesced rows (the barrier has waited for this
+        // wave's staging writes)
+        {
+            bf16_t *py = y + (size_t)t.tok0 * xrow + xlane;
+            if (t.len == kQ) {  // full tile: no predication
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    *reinterpret_cast<uint4 *>(py + (size_t)(tok_l + 16 * m) * xrow) =
+                        *reinterpret_cast<const uint4 *>(&W.Ys[tok_l + 16 * m][xcol]);
+            } else {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int tok = tok_l + 16 * m;
+                    if (tok < t.len)
+                        *reinterpret_cast<uint4 *>(py + (size_t)tok * xrow) = *reinterpret_cast<const uint4 *>(&W.Ys[tok][xcol]);
+                }
+            }
+        }
+        SSM_TRACE(7);
+        phase_end();
+        SSM_TRACE(15);
+    }
+    for (int b = 0; b < kStagger * (kWaves - 1 - w); ++b)
+        lds_barrier();
+    if (touched == 0x9e3779b9u && n_wg < 0)  // never true (the grid is not empty): keeps the warm-up loads alive
+        *reinterpret_cast<uint32_t *>(y) = touched;
+    SSM_TRACE_FLUSH
+}
+
+template <int ST>
+hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
+                          hipStream_t stream)
+{
+    static std::once_flag attr_once[64];
+    static hipError_t attr_err[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    std::call_once(attr_once[dev], [&]() {
+        attr_err[dev] = hipFuncSetAttribute(reinterpret_cast<const void *>(ssm_scan_mfma_kernel<ST>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+    });
+    if (attr_err[dev] != hipSuccess)
+        return attr_err[dev];
+    const int n_wg = plan->n_workgroups;
+    const int per_xcd = (n_wg + 7) / 8;
+    hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), sizeof(Lds), stream,
+                       static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y), args.state_out,
+                       args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G, args.p_split, per_xcd,
+                       n_wg);
+    return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *, hipStream_t stream)
+hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream)
 {
-    static bool attr_set = false;
-    const size_t lds = sizeof(Lds);
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ssm_scan_mfma_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
+    const int n_tiles = (int)plan->tiles.size();
+    if (n_tiles == 0 || plan->n_workgroups == 0)
+        return hipSuccess;
+    uint4 *frags = static_cast<uint4 *>(workspace);
+    bf16_t *dt_t = reinterpret_cast<bf16_t *>(static_cast<unsigned char *>(workspace) +
+                                              (size_t)n_tiles * args.G * kMfmaTileGroupBytes);
+    hipLaunchKernelGGL(ssm_prep_kernel, dim3((unsigned)n_tiles * (unsigned)args.G), dim3(kPrepThreads), sizeof(PrepLds),
+                       stream, static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C),
+                       static_cast<const bf16_t *>(args.dt), args.tiles, frags, dt_t, args.H, args.G, n_tiles);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    switch (args.state_dtype) {
+    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16>(plan, args, frags, dt_t, stream);
+    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16>(plan, args, frags, dt_t, stream);
+    default: return launch_scan_st<SSM_ST_F32>(plan, args, frags, dt_t, stream);
     }
-    const int n_wg = plan->n_workgroups;
-    const int per_xcd = (n_wg + 7) / 8;
-    hipLaunchKernelGGL(ssm_scan_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
-                       static_cast<const bf16_t *>(args.x), static_cast<const bf16_t *>(args.dt), args.A,
-                       static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C), args.D,
-                       static_cast<bf16_t *>(args.y), static_cast<float *>(args.state_out),
-                       reinterpret_cast<const float *const *>(args.init_ptrs), args.tiles, args.seqs,
-                       args.H, args.P, args.G, args.p_split, per_xcd, n_wg);
-    return hipGetLastError();
 }

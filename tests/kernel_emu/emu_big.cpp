@@ -1,5 +1,6 @@
 // Spot check of the matrix-core scan kernel at full problem sizes on the emulator (test infrastructure only): only
-// the first two and the last workgroup of the scan run, every buffer is guarded, and the outputs of those workgroups are compared with a plain fp64 recurrence
+// the first two and the last workgroup of the scan run (and the workgroups of the kernel in front of it that they
+// depend on), every buffer is guarded, and the outputs of those workgroups are compared with a plain fp64 recurrence
 // computed here.  Inputs are drawn only where those workgroups read them.   emu_big <T> <ckpt_every> [H P G]
 #include <hip/hip_runtime.h>
 #include <cmath>
@@ -14,7 +15,11 @@ static int gH, gP, gG, g_per_xcd, g_psplit;
 static std::vector<int> g_wgs;   // logical workgroup ids to run
 static bool filter(int launch, unsigned b)
 {
-    (void)launch;
+    if (launch == 0) {  // the kernel in front of the scan: block = tile * G + g; keep the groups of the selected heads
+        const int g = b % gG;
+        for (int wg : g_wgs) if (((wg / g_psplit) % gH) / (gH / gG) == g) return true;
+        return false;
+    }
     const int wg = (b & 7) * g_per_xcd + (b >> 3);
     for (int w : g_wgs) if (w == wg) return true;
     return false;

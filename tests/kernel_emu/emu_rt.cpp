@@ -30,7 +30,7 @@
 namespace emu {
 namespace {
 enum St { RUN, W_WAVE, W_BARRIER, DONE };
-enum Op { OP_NONE, OP_SYNC, OP_MFMA32, OP_MFMA16, OP_TR, OP_DPP, OP_READLANE, OP_READFIRST, OP_SHFL };
+enum Op { OP_NONE, OP_SYNC, OP_MFMA32, OP_MFMA32H, OP_MFMA16, OP_TR, OP_DPP, OP_READLANE, OP_READFIRST, OP_SHFL };
 
 struct Coll {
     int op = OP_NONE, line = 0;
@@ -100,15 +100,24 @@ void run_collective(Lane *L)
             die("lanes of a wave wait on different cross-lane operations", k0.line, L[l].k.line);
     switch (k0.op) {
     case OP_SYNC: break;
-    case OP_MFMA32: {
+    case OP_MFMA32:
+    case OP_MFMA32H: {
         // A: lane l holds row l%32, k = 8(l/32)+e.  B: lane l holds column l%32, same k.
-        // C/D: lane l, element r: column l%32, row 8(r/4) + 4(l/32) + r%4.
+        // C/D: lane l, element r: column l%32, row 8(r/4) + 4(l/32) + r%4.  Same layouts for bf16 and fp16 operands.
         static double acc[32][32];
         for (int i = 0; i < 32; ++i)
             for (int j = 0; j < 32; ++j)
                 acc[i][j] = 0.0;
         float A[32][16], B[16][32];
         for (int l = 0; l < 64; ++l) {
+            if (k0.op == OP_MFMA32H) {
+                const f16x8 a = *static_cast<const f16x8 *>(L[l].k.a), b = *static_cast<const f16x8 *>(L[l].k.b);
+                for (int e = 0; e < 8; ++e) {
+                    A[l % 32][8 * (l / 32) + e] = (float)a[e];
+                    B[8 * (l / 32) + e][l % 32] = (float)b[e];
+                }
+                continue;
+            }
             const bf16x8 a = *static_cast<const bf16x8 *>(L[l].k.a), b = *static_cast<const bf16x8 *>(L[l].k.b);
             for (int e = 0; e < 8; ++e) {
                 A[l % 32][8 * (l / 32) + e] = bf(a[e]);
@@ -364,6 +373,14 @@ f32x16 mfma_32x32x16_bf16(bf16x8 a, bf16x8 b, f32x16 c, int line)
     f32x16 res;
     cur->k.a = &a, cur->k.b = &b, cur->k.c = &c, cur->k.res = &res;
     collective(OP_MFMA32, line);
+    return res;
+}
+
+f32x16 mfma_32x32x16_f16(f16x8 a, f16x8 b, f32x16 c, int line)
+{
+    f32x16 res;
+    cur->k.a = &a, cur->k.b = &b, cur->k.c = &c, cur->k.res = &res;
+    collective(OP_MFMA32H, line);
     return res;
 }
 

@@ -33,6 +33,8 @@ struct dim3 {
 typedef int hipError_t;
 constexpr hipError_t hipSuccess = 0;
 constexpr hipError_t hipErrorInvalidValue = 1;
+constexpr hipError_t hipErrorInvalidDevice = 101;
+static inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 typedef void *hipStream_t;
 constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
@@ -40,6 +42,7 @@ static inline hipError_t hipGetLastError() { return hipSuccess; }
 
 namespace emu {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -52,6 +55,7 @@ unsigned char *lds_base();
 void barrier(int line);     // workgroup barrier
 void wave_sync(int line);   // lockstep point inside a wave (stands for an LDS wait between lanes of one wave)
 f32x16 mfma_32x32x16_bf16(bf16x8 a, bf16x8 b, f32x16 c, int line);
+f32x16 mfma_32x32x16_f16(f16x8 a, f16x8 b, f32x16 c, int line);
 f32x4 mfma_16x16x32_bf16(bf16x8 a, bf16x8 b, f32x4 c, int line);
 s16x4 ds_read_tr16_b64(const void *p, int line);
 int update_dpp(int old, int src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl, int line);
@@ -72,6 +76,7 @@ template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&b
 #define __syncthreads() emu::barrier(__LINE__)
 
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) emu::mfma_32x32x16_bf16((a), (b), (c), __LINE__)
+#define __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, x, y, z) emu::mfma_32x32x16_f16((a), (b), (c), __LINE__)
 #define __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, x, y, z) emu::mfma_16x16x32_bf16((a), (b), (c), __LINE__)
 #define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) emu::ds_read_tr16_b64((const void *)(p), __LINE__)
 #define __builtin_amdgcn_update_dpp(old, src, ctrl, rm, bm, bc) emu::update_dpp((old), (src), (ctrl), (rm), (bm), (bc), __LINE__)
@@ -81,6 +86,7 @@ template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&b
 #define __builtin_amdgcn_exp2f(x) exp2f(x)
 #define __builtin_amdgcn_rcpf(x) (1.0f / (x))
 #define __builtin_amdgcn_s_setprio(x) ((void)0)
+#define __builtin_amdgcn_sched_barrier(x) ((void)0)
 #define __builtin_amdgcn_logf(x) log2f(x)
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \

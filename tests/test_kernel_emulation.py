@@ -94,6 +94,12 @@ def emu_binary(tmp_path_factory):
 
 
 @pytest.fixture(scope="session")
+def emu_binary_8waves(tmp_path_factory):
+    """The matrix-core scan with 8 waves per workgroup (one tile finishes per round of its phase schedule)."""
+    return _build(tmp_path_factory, "kernel_emu8", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=8"])
+
+
+@pytest.fixture(scope="session")
 def emu_conv_binary(tmp_path_factory):
     """The convolution kernel with its own driver."""
     if not os.path.exists(CLANG):
@@ -381,15 +387,22 @@ def test_full_size_spot_check(tmp_path_factory):
     assert r.returncode == 0 and "BIG CHECK OK" in r.stdout, r.stdout[-1500:] + r.stderr[-500:]
 
 
-def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
-    """Self-test of the race check on the bf16 kernel: with the barrier of one
-    pipeline step made not to wait, forward and reverse wave order disagree."""
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_emulated_8wave_scan_matches_oracle_in_any_wave_order(emu_binary_8waves, tmp_path, case):
+    _check_case(emu_binary_8waves, tmp_path, "bf16", case)
+
+
+def test_a_barrier_that_does_not_wait_is_noticed(emu_binary_8waves, tmp_path):
+    """Self-test of the race check on the bf16 kernel: with the barrier between the state hand-offs of two
+    consecutive tiles made not to wait, forward and reverse wave order disagree.  (With 8 waves a tile hands the
+    state over in every round; rounds 5, 6 and 7 are the hand-offs of tiles 0/1, 1/2 and 2/3.)"""
+    emu_binary = emu_binary_8waves
     shape = LayerShape(nheads=1, headdim=32, d_state=128, ngroups=1, chunk=64, io_dtype="bf16")
     wl = make_workload(4, "cpu", seed=5, shape=shape, seqlen=450, ckpt_every=200)
     init = list(wl.init_state)
     ref = _emulate(emu_binary, wl, init, tmp_path, 0, "end")[2]
     noticed = 0
-    for drop in (3, 4, 5):
+    for drop in (5, 6, 7):
         outs = [_emulate(emu_binary, wl, init, tmp_path, order, "end", drop)[2] for order in (0, 1)]
         noticed += not (np.array_equal(outs[0], ref) and np.array_equal(outs[1], ref))
     assert noticed == 3
