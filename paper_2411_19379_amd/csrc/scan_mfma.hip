@@ -57,7 +57,7 @@ constexpr int kQ = kMfmaTileTokens;  // 64 tokens per tile
 constexpr int kN = 128;              // d_state
 constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_SCAN_WAVES
-#define SSM_SCAN_WAVES 4
+#define SSM_SCAN_WAVES 8
 #endif
 constexpr int kWaves = SSM_SCAN_WAVES;   // waves per workgroup of the scan: 4 or 8
 constexpr int kThreads = 64 * kWaves;

@@ -95,8 +95,8 @@ def emu_binary(tmp_path_factory):
 
 @pytest.fixture(scope="session")
 def emu_binary_8waves(tmp_path_factory):
-    """The matrix-core scan with 8 waves per workgroup (one tile finishes per round of its phase schedule)."""
-    return _build(tmp_path_factory, "kernel_emu8", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=8"])
+    """The matrix-core scan with 4 waves per workgroup instead of the shipped 8."""
+    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4"])
 
 
 @pytest.fixture(scope="session")
