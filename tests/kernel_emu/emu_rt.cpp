@@ -30,7 +30,7 @@
 namespace emu {
 namespace {
 enum St { RUN, W_WAVE, W_BARRIER, DONE };
-enum Op { OP_NONE, OP_SYNC, OP_MFMA32, OP_MFMA32H, OP_MFMA16, OP_TR, OP_DPP, OP_READLANE, OP_READFIRST, OP_SHFL };
+enum Op { OP_NONE, OP_SYNC, OP_MFMA32, OP_MFMA32H, OP_MFMA16, OP_TR, OP_DPP, OP_READLANE, OP_READFIRST, OP_SHFL, OP_YIELD };
 
 struct Coll {
     int op = OP_NONE, line = 0;
@@ -248,8 +248,9 @@ void run_collective(Lane *L)
     }
 }
 
-// run one wave until all its lanes sit at a barrier or are done
-void run_wave(int w, int n_lanes)
+// run one wave until all its lanes sit at a barrier, are done, or have yielded (a spin-wait gives the other waves a
+// turn); returns true in the last case
+bool run_wave(int w, int n_lanes)
 {
     Lane *L = &lanes[64 * w];
     const int nl = std::min(64, n_lanes - 64 * w);
@@ -271,6 +272,16 @@ void run_wave(int w, int n_lanes)
         if (n_wave == nl) {
             if (nl != 64)
                 die("cross-lane operation in a partial wave");
+            if (L[0].k.op == OP_YIELD) {
+                for (int l = 1; l < 64; ++l)
+                    if (L[l].k.op != OP_YIELD)
+                        die("lanes of a wave wait on different cross-lane operations", L[0].k.line, L[l].k.line);
+                for (int l = 0; l < 64; ++l) {
+                    L[l].k.op = OP_NONE;
+                    L[l].st = RUN;
+                }
+                return true;
+            }
             run_collective(L);
             continue;
         }
@@ -280,7 +291,7 @@ void run_wave(int w, int n_lanes)
         if (n_bar + n_done == nl) {
             if (n_bar != 0 && n_done != 0)
                 die("some lanes of a wave are done while others wait at a barrier", w);
-            return;
+            return false;
         }
         if (!progressed)
             die("wave makes no progress", w);
@@ -306,14 +317,20 @@ void run_block(dim3 block)
     }
     std::vector<int> order(n_waves);
     std::mt19937 rng((unsigned)g_order_mode * 7919u + g_block.x);
-    long epoch = 0;
+    long epoch = 0, yield_passes = 0;
     for (;;) {
         for (int w = 0; w < n_waves; ++w)
             order[w] = g_order_mode == 1 ? n_waves - 1 - w : w;
         if (g_order_mode >= 2)
             std::shuffle(order.begin(), order.end(), rng);
+        bool yielded = false;
         for (int w : order)
-            run_wave(w, n_lanes);
+            yielded = run_wave(w, n_lanes) || yielded;
+        if (yielded) {  // a wave is spinning on something another wave will write: give everybody another turn
+            if (++yield_passes > 50000000L)
+                die("waves keep yielding: a spin-wait that nothing ends (a hang on the GPU)");
+            continue;
+        }
         int n_bar = 0, n_done = 0, line = -1;
         for (Lane &ln : lanes) {
             if (ln.st == W_BARRIER) {
@@ -367,6 +384,7 @@ static void collective(int op, int line)
 }
 
 void wave_sync(int line) { collective(OP_SYNC, line); }
+void wave_yield(int line) { collective(OP_YIELD, line); }
 
 f32x16 mfma_32x32x16_bf16(bf16x8 a, bf16x8 b, f32x16 c, int line)
 {

@@ -54,6 +54,7 @@ unsigned char *lds_base();
 
 void barrier(int line);     // workgroup barrier
 void wave_sync(int line);   // lockstep point inside a wave (stands for an LDS wait between lanes of one wave)
+void wave_yield(int line);  // inside a spin-wait: the other waves of the workgroup get a turn
 f32x16 mfma_32x32x16_bf16(bf16x8 a, bf16x8 b, f32x16 c, int line);
 f32x16 mfma_32x32x16_f16(f16x8 a, f16x8 b, f32x16 c, int line);
 f32x4 mfma_16x16x32_bf16(bf16x8 a, bf16x8 b, f32x4 c, int line);
@@ -87,6 +88,7 @@ template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&b
 #define __builtin_amdgcn_rcpf(x) (1.0f / (x))
 #define __builtin_amdgcn_s_setprio(x) ((void)0)
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
+#define __builtin_amdgcn_s_sleep(x) emu::wave_yield(__LINE__)
 #define __builtin_amdgcn_logf(x) log2f(x)
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \

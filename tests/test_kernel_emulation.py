@@ -48,6 +48,7 @@ _SUBST = [
     (r'asm volatile\("s_waitcnt lgkmcnt\(0\)\\n\\ts_barrier" ::: "memory"\);', "emu::barrier(__LINE__);"),
     (r'asm volatile\("s_waitcnt lgkmcnt\(0\)" ::: "memory"\);', "emu::wave_sync(__LINE__);"),
     (r"extern __shared__ __align__\(16\) unsigned char lds_raw\[\];", "unsigned char *lds_raw = emu::lds_base();"),
+    (r'asm volatile\("" ::: "memory"\);', ";"),  # compiler-only fence: nothing to emulate
 ]
 
 
@@ -392,17 +393,16 @@ def test_emulated_8wave_scan_matches_oracle_in_any_wave_order(emu_binary_8waves,
     _check_case(emu_binary_8waves, tmp_path, "bf16", case)
 
 
-def test_a_barrier_that_does_not_wait_is_noticed(emu_binary_8waves, tmp_path):
-    """Self-test of the race check on the bf16 kernel: with the barrier between the state hand-offs of two
-    consecutive tiles made not to wait, forward and reverse wave order disagree.  (With 8 waves a tile hands the
-    state over in every round; rounds 5, 6 and 7 are the hand-offs of tiles 0/1, 1/2 and 2/3.)"""
-    emu_binary = emu_binary_8waves
+def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
+    """Self-test of the race check on the bf16 kernel.  The scan has one workgroup barrier, between the write of the
+    starting state into LDS and the first hand-off; with it made not to wait, a wave reads the state before it is
+    there (LDS starts as a NaN pattern) in at least one wave order."""
     shape = LayerShape(nheads=1, headdim=32, d_state=128, ngroups=1, chunk=64, io_dtype="bf16")
     wl = make_workload(4, "cpu", seed=5, shape=shape, seqlen=450, ckpt_every=200)
-    init = list(wl.init_state)
+    g = torch.Generator().manual_seed(9)
+    init = [torch.randn((1, 32, 128), generator=g)]
     ref = _emulate(emu_binary, wl, init, tmp_path, 0, "end")[2]
-    noticed = 0
-    for drop in (5, 6, 7):
-        outs = [_emulate(emu_binary, wl, init, tmp_path, order, "end", drop)[2] for order in (0, 1)]
-        noticed += not (np.array_equal(outs[0], ref) and np.array_equal(outs[1], ref))
-    assert noticed == 3
+    # every block counts its barriers from zero: ordinal 0 is the scan's only one (and the first of the kernel in
+    # front of it, whose second one publishes nothing the dropped one did not)
+    outs = [_emulate(emu_binary, wl, init, tmp_path, order, "end", 0)[2] for order in (0, 1, 5)]
+    assert not all(np.array_equal(o, ref) for o in outs)
