@@ -109,15 +109,25 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 
 // Global loads of the scan.  They are issued phases ahead of their use; the scheduling fences at the phase ends keep
 // them where they are written.
-// Addresses are a wave-uniform base (scalar registers) plus a 32-bit byte offset per lane, so that no 64-bit
-// address arithmetic runs on the vector ALUs.
-__device__ __forceinline__ uint4 load16_here(const unsigned char *base, uint32_t off)
+// Loads and stores of the tile loop go through buffer descriptors: a wave-uniform base and size in scalar registers,
+// one 32-bit byte offset per lane and a uniform offset, so that no address arithmetic runs on the vector ALUs.  Every
+// access stays inside its descriptor's range; nothing relies on what the hardware does beyond it.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    return *reinterpret_cast<const uint4 *>(base + off);
+    // raw buffer (stride 0) of `bytes` bytes; the flags word selects 32-bit data, as for any untyped access on gfx9
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
-__device__ __forceinline__ uint32_t load4_here(const unsigned char *base, uint32_t off)
+__device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off)
 {
-    return *reinterpret_cast<const uint32_t *>(base + off);
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)uniform_off, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void buf_store16(rsrc_t r, uint32_t lane_off, uint32_t uniform_off, const uint4 &d)
+{
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = {d.x, d.y, d.z, d.w};
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, (int)uniform_off, 0);
 }
 
 // Wait for this wave's own LDS traffic (LDS executes a wave's accesses in order).
@@ -457,47 +467,61 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
         L.done[threadIdx.x] = 0;
     lds_barrier();  // the only workgroup barrier: the starting state and the counters are in place
     SSM_TRACE_DECL
-    SsmTile t_next = tiles[__builtin_amdgcn_readfirstlane(tile_begin + (w < n_tiles ? w : 0))];
-    for (int k = w; k < n_tiles; k += kWaves) {  // this wave's tiles
-        __builtin_amdgcn_sched_barrier(0);
-        const int tile_idx = __builtin_amdgcn_readfirstlane(tile_begin + k);
-        const SsmTile t = t_next;  // read during the previous tile of this wave
-        const unsigned char *img =
-            reinterpret_cast<const unsigned char *>(frags) + ((size_t)tile_idx * G + g) * kMfmaTileGroupBytes;
-        constexpr uint32_t kBfOff = kCfWords * 16, kCbOff = (kCfWords + kBfWords) * 16;
-        SSM_TRACE(8);
+    constexpr uint32_t kBfOff = kCfWords * 16, kCbOff = (kCfWords + kBfWords) * 16;
+    const unsigned char *img_g = reinterpret_cast<const unsigned char *>(frags) + (size_t)g * kMfmaTileGroupBytes;
 
-        // ---------------- phase 0: this tile's loads of dt, x, the raw scores and the B^T operand.  Rows past the
-        // end of a partial tile re-read the tile's last row: their weights are zero, so any finite value will do.
-        const uint32_t dt_raw = (dt_t + ((size_t)tile_idx * H + h) * kQ)[lane];
-        uint4 xr[4];
-        {
-            const unsigned char *xt = xh + (size_t)t.tok0 * xrow_b;
-            if (t.len == kQ) {
+    // What a tile needs first (dt, x, the raw scores and the B^T operand) is loaded one tile of this wave ahead:
+    // the loads of the next tile are issued before the epilogue of the current one and are in flight under it.
+    uint32_t dt_raw = 0;
+    uint4 xr[4], cb[3][2], bf[4][4];
+    auto issue_first_loads = [&](int tile_idx, const SsmTile &tl, bool live) {
+        const rsrc_t img =
+            make_rsrc(img_g + (size_t)tile_idx * G * kMfmaTileGroupBytes, live ? kMfmaTileGroupBytes : 0);
+        const rsrc_t dtr = make_rsrc(dt_t + ((size_t)tile_idx * H + h) * kQ, live ? kQ * 2 : 0);
+        dt_raw = __builtin_amdgcn_raw_buffer_load_b16(dtr, lane * 2, 0, 0);
+        // Rows past the end of a partial tile re-read the tile's last row: their weights are zero, so any finite
+        // value will do.
+        const rsrc_t xrs =
+            make_rsrc(xh + (size_t)tl.tok0 * xrow_b, live ? (uint32_t)(tl.len - 1) * xrow_b + kPW * 2 : 0);
+        if (tl.len == kQ) {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    xr[kk] = load16_here(xt + (size_t)(16 * kk) * xrow_b, xoff_lane);
-            } else {
+            for (int kk = 0; kk < 4; ++kk)
+                xr[kk] = buf_load16(xrs, xoff_lane, (uint32_t)(16 * kk) * xrow_b);
+        } else {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int tok = tok_l + 16 * kk < t.len ? tok_l + 16 * kk : t.len - 1;
-                    xr[kk] = load16_here(xt, (uint32_t)tok * xrow_b + xcol * 2);
-                }
+            for (int kk = 0; kk < 4; ++kk) {
+                const int tok = tok_l + 16 * kk < tl.len ? tok_l + 16 * kk : tl.len - 1;
+                xr[kk] = buf_load16(xrs, (uint32_t)tok * xrow_b + xcol * 2, 0);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);  // dt and x first: the next phase waits for them, not for what follows
-        uint4 cb[3][2];
+        __builtin_amdgcn_sched_barrier(0);  // dt and x first: the tile waits for them before anything else
 #pragma unroll
         for (int blk = 0; blk < 3; ++blk)
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
-                cb[blk][hf] = load16_here(img, lane16 + kCbOff + (blk * 2 + hf) * 1024);
-        uint4 bf[4][4];
+                cb[blk][hf] = buf_load16(img, lane16, kCbOff + (blk * 2 + hf) * 1024);
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                bf[nb][ks] = load16_here(img, lane16 + kBfOff + (nb * 4 + ks) * 1024);
+                bf[nb][ks] = buf_load16(img, lane16, kBfOff + (nb * 4 + ks) * 1024);
+    };
+    if (w >= n_tiles)
+        return;  // a wave without tiles; no barrier follows
+    int tile_idx = __builtin_amdgcn_readfirstlane(tile_begin + w);
+    SsmTile t = tiles[tile_idx], t_next = t;
+    issue_first_loads(tile_idx, t, true);
+    for (int k = w; k < n_tiles; k += kWaves) {  // this wave's tiles
+        __builtin_amdgcn_sched_barrier(0);
+        const rsrc_t img = make_rsrc(img_g + (size_t)tile_idx * G * kMfmaTileGroupBytes, kMfmaTileGroupBytes);
+        SSM_TRACE(8);
+        // C for the first half of the state indices: needed at the first hand-off
+        uint4 cfr[2][2][4];  // [half of the state indices][token half][k-step]
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                cfr[0][ih][ks] = buf_load16(img, lane16, (ih * 8 + ks) * 1024);
         SSM_TRACE(0);
         phase_end();
 
@@ -539,7 +563,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
         phase_end();
 
         // ---------------- phase 2: tile-local state sum_j (e^{l_q-l_j} dt_j x_j) B_j^T on the matrix cores; under
-        // it, the loads of C for the first half of the state indices and the masked scores of the first token half
+        // it, the loads of C for the second half of the state indices and the masked scores of the first token half
         f32x16 Sl[4];
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb)
@@ -549,12 +573,12 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
                 Sl[nb] = mfma_f16(bf[nb][ks], xw[ks], Sl[nb]);
-        uint4 cfr[2][2][4];  // [half of the state indices][token half][k-step]
+        __builtin_amdgcn_sched_barrier(0);  // the B^T operand's registers are free from here on
 #pragma unroll
         for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                cfr[0][ih][ks] = load16_here(img, lane16 + (ih * 8 + ks) * 1024);
+                cfr[1][ih][ks] = buf_load16(img, lane16, (ih * 8 + 4 + ks) * 1024);
         uint4 gd[2][2], go[2];
         if (fast)
             mask_diag<true>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
@@ -641,24 +665,23 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
                 Yo[1] = mfma_f16(s16, cfr[nb >> 1][1][2 * (nb & 1) + hf], Yo[1]);
             }
         };
-        {
-            // C for the other half of the state indices arrives during the next phase
-#pragma unroll
-            for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    cfr[1][ih][ks] = load16_here(img, lane16 + (ih * 8 + 4 + ks) * 1024);
-            if (k + kWaves < n_tiles)  // the descriptor of this wave's next tile
-                t_next = tiles[__builtin_amdgcn_readfirstlane(tile_idx + kWaves)];
-            SSM_TRACE(4);
-            hand_off(0);
-        }
+        const bool more = k + kWaves < n_tiles;
+        if (more)  // the descriptor of this wave's next tile
+            t_next = tiles[tile_idx + kWaves];
+        SSM_TRACE(4);
+        hand_off(0);
         hand_off(1);
         SSM_TRACE(5);
         phase_end();
         hand_off(2);
+        hand_off(3);
+        phase_end();
+        // The loads of this wave's next tile.  After its last tile the wave issues them once more with descriptors of
+        // size zero (and the current tile's addresses): such loads return zeros without touching memory, and the
+        // loop needs no second copy of its tail.
+        issue_first_loads(more ? tile_idx + kWaves : tile_idx, t_next, more);
+        phase_end();
         {   // y = e^{l_i} (S C_i) + intra-tile term on its way to LDS
-            hand_off(3);
 #pragma unroll
             for (int ih = 0; ih < 2; ++ih) {
                 const float ei = W.ei[32 * ih + i];
@@ -678,24 +701,26 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
 
         // ---------------- y from LDS to device memory in coalesced rows
         {
-            unsigned char *yt = yh + (size_t)t.tok0 * xrow_b;
+            const rsrc_t yrs = make_rsrc(yh + (size_t)t.tok0 * xrow_b, (uint32_t)(t.len - 1) * xrow_b + kPW * 2);
             if (t.len == kQ) {  // full tile: no predication
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    *reinterpret_cast<uint4 *>(yt + (size_t)(16 * m) * xrow_b + xoff_lane) =
-                        *reinterpret_cast<const uint4 *>(&W.Ys[tok_l + 16 * m][xcol]);
+                    buf_store16(yrs, xoff_lane, (uint32_t)(16 * m) * xrow_b,
+                                *reinterpret_cast<const uint4 *>(&W.Ys[tok_l + 16 * m][xcol]));
             } else {
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int tok = tok_l + 16 * m;
                     if (tok < t.len)
-                        *reinterpret_cast<uint4 *>(yt + (size_t)(16 * m) * xrow_b + xoff_lane) =
-                            *reinterpret_cast<const uint4 *>(&W.Ys[tok][xcol]);
+                        buf_store16(yrs, xoff_lane, (uint32_t)(16 * m) * xrow_b,
+                                    *reinterpret_cast<const uint4 *>(&W.Ys[tok][xcol]));
                 }
             }
         }
         SSM_TRACE(7);
         phase_end();
+        t = t_next;
+        tile_idx += kWaves;
     }
     SSM_TRACE_FLUSH
 }

@@ -364,6 +364,13 @@ void set_order_mode(int m) { g_order_mode = m; }
 void set_block_filter(bool (*filter)(int, unsigned)) { g_block_filter = filter; }
 long switches() { return g_switches; }
 
+void buffer_range_fault(uint32_t off, uint32_t n, uint32_t bytes, int line)
+{
+    fprintf(stderr, "emu: buffer access of %u bytes at offset %u beyond a descriptor of %u bytes (source line %d)\n", n,
+            off, bytes, line);
+    abort();
+}
+
 void set_drop_barrier(long n) { g_drop_barrier = n; }
 
 void barrier(int line)

@@ -64,6 +64,40 @@ int readlane(int v, int lane, int line);
 int readfirstlane(int v, int line);
 int shfl(int v, int src_lane, int line);  // any-to-any lane read (ds_bpermute)
 
+// Buffer descriptor of the raw (stride 0) kind: a base and a size in bytes.  An access that lies inside [0, bytes)
+// goes to memory; a load through a descriptor of size zero returns zeros without touching memory, as the hardware's
+// range check does; any other access beyond the size is a bug of the kernel and ends the run.
+struct BufRsrc {
+    unsigned char *base;
+    uint32_t bytes;
+};
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+void buffer_range_fault(uint32_t off, uint32_t n, uint32_t bytes, int line);
+static inline BufRsrc make_buffer_rsrc(void *base, int stride, int bytes, int flags)
+{
+    (void)stride, (void)flags;
+    return {static_cast<unsigned char *>(base), (uint32_t)bytes};
+}
+template <typename T> static inline T buffer_load(const BufRsrc &r, int voff, int soff, int line)
+{
+    T v;
+    memset(&v, 0, sizeof v);
+    if (r.bytes == 0)
+        return v;
+    const uint32_t off = (uint32_t)voff + (uint32_t)soff;
+    if ((uint64_t)off + sizeof(T) > r.bytes)
+        buffer_range_fault(off, sizeof(T), r.bytes, line);
+    memcpy(&v, r.base + off, sizeof v);
+    return v;
+}
+template <typename T> static inline void buffer_store(const T &v, const BufRsrc &r, int voff, int soff, int line)
+{
+    const uint32_t off = (uint32_t)voff + (uint32_t)soff;
+    if ((uint64_t)off + sizeof(T) > r.bytes)
+        buffer_range_fault(off, sizeof(T), r.bytes, line);
+    memcpy(r.base + off, &v, sizeof v);
+}
+
 template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&body);
 void launch_impl(dim3 grid, dim3 block, size_t lds_bytes, void (*fn)(void *), void *arg);
 template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&body)
@@ -84,6 +118,11 @@ template <typename F> void launch(dim3 grid, dim3 block, size_t lds_bytes, F &&b
 #define __builtin_amdgcn_readlane(v, l) emu::readlane((v), (l), __LINE__)
 #define __builtin_amdgcn_readfirstlane(v) emu::readfirstlane((v), __LINE__)
 #define __shfl(v, l, w) __uint_as_float((uint32_t)emu::shfl((int)__float_as_uint(v), (l), __LINE__))
+#define __amdgpu_buffer_rsrc_t emu::BufRsrc
+#define __builtin_amdgcn_make_buffer_rsrc(p, stride, n, flags) emu::make_buffer_rsrc((p), (stride), (n), (flags))
+#define __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, aux) emu::buffer_load<emu::u32x4>((r), (voff), (soff), __LINE__)
+#define __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, aux) emu::buffer_load<unsigned short>((r), (voff), (soff), __LINE__)
+#define __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, aux) emu::buffer_store((v), (r), (voff), (soff), __LINE__)
 #define __builtin_amdgcn_exp2f(x) exp2f(x)
 #define __builtin_amdgcn_rcpf(x) (1.0f / (x))
 #define __builtin_amdgcn_s_setprio(x) ((void)0)
