@@ -2,26 +2,51 @@
 """Benchmark of the SSM-layer prefill on one MI355X.
 
 A step is one pass of the whole hot path (plan reuse, one `ssm_prefill` call:
-decay prefix, masked scores, intra-chunk term, chunk states, state passing,
-checkpoint emission, fused output) over one batch of synthetic input that is
-already resident in HBM.  Prints ONE JSON line.
+operand preparation, decay prefix, masked scores, intra-chunk term, chunk
+states, state passing, checkpoint emission, fused output) over one batch of
+synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+                    [--no-checkpoints] [--calibrate-copy] [--no-cpu-baseline]
+
+`--no-checkpoints` drops every checkpoint of the configuration (the cost of
+checkpoint emission is the difference to the run with them).
+`--calibrate-copy` also runs a plain device copy of 1 GiB a few times, which a
+counter run (`rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`) needs to turn
+counter units into bytes.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
+import os
 import sys
 import time
 
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 / fp16, published
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+# HBM bytes per launch of the scan kernel, from two counter runs of this file
+# (profiles/ssm_scan_mfma_kernel_*_pmc.txt gives the commands and the raw
+# readings): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each divided by
+# what the same counter reads per KiB actually moved by the 1 GiB copy of
+# --calibrate-copy.  Keyed by the hash of the kernel source the counters were
+# taken on: once that source changes the figure is reported as null.
+MEASURED_TRAFFIC = {
+    # "sha1 of scan_mfma.hip": {"cfg3_7b_32k_bf16": {"fetch_bytes": ..., "write_bytes": ...}},
+}
 
 
-def algorithmic_bytes(wl) -> int:
+def kernel_source_hash() -> str:
+    with open(os.path.join(ROOT, "paper_2411_19379_amd", "csrc", "scan_mfma.hip"), "rb") as f:
+        return hashlib.sha1(f.read()).hexdigest()
+
+
+def algorithmic_bytes(wl, n_ckpt: int) -> int:
     """Compulsory HBM bytes of one call: x and y once, dt, B, C once, every
     non-null initial state read once, every checkpoint written once."""
     s = wl.shape
@@ -29,7 +54,7 @@ def algorithmic_bytes(wl) -> int:
     per_token = (2 * s.nheads * s.headdim + s.nheads + 2 * s.ngroups * s.d_state) * esz
     state = s.nheads * s.headdim * s.d_state * 4
     n_init = sum(1 for k in wl.init_kind if k != "zeros")
-    return wl.total_tokens * per_token + (n_init + wl.n_ckpt) * state
+    return wl.total_tokens * per_token + (n_init + n_ckpt) * state
 
 
 def algorithmic_flops(wl, tile: int) -> float:
@@ -41,9 +66,10 @@ def algorithmic_flops(wl, tile: int) -> float:
     return float(wl.total_tokens) * s.nheads * per_th
 
 
-def cpu_baseline(wl, sample_tokens: int):
+def cpu_baseline(wl, sample_tokens: int, min_seconds: float = 10.0, max_repeats: int = 16):
     """The oracle as it stands on the host cores, on the first `sample_tokens`
-    tokens of the first sequence (all heads, zero initial state)."""
+    tokens of the first sequence (all heads, zero initial state), repeated
+    until about `min_seconds` of CPU work have been timed."""
     import oracle
 
     n = min(sample_tokens, wl.seqlens[0])
@@ -56,12 +82,17 @@ def cpu_baseline(wl, sample_tokens: int):
     D = wl.D.cpu().numpy()
     threads = oracle.max_threads()
     oracle.ssm_prefill_oracle(x[:16], dt[:16], A, B[:16], C[:16], D, [0, 16], None, [[16]])  # load + warm
+    reps = 0
     t0 = time.perf_counter()
-    oracle.ssm_prefill_oracle(x, dt, A, B, C, D, [0, n], None, [[n]], nthreads=threads)
+    while reps < max_repeats:
+        oracle.ssm_prefill_oracle(x, dt, A, B, C, D, [0, n], None, [[n]], nthreads=threads)
+        reps += 1
+        if time.perf_counter() - t0 >= min_seconds:
+            break
     el = time.perf_counter() - t0
-    return {"value": n / el, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    return {"value": n * reps / el, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"first {n} tokens of the workload, all {wl.shape.nheads} heads, zero initial state, "
-                      f"one checkpoint; {el:.1f} s"}
+                      f"one checkpoint, {reps} passes; {el:.1f} s"}
 
 
 def main() -> int:
@@ -70,6 +101,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="named configuration 0..4 (default: the 7B 32K one)")
+    ap.add_argument("--no-checkpoints", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     args = ap.parse_args()
@@ -91,6 +124,8 @@ def main() -> int:
     wl = make_workload(args.config, dev)
     s = wl.shape
     inp = wl.inputs
+    ckpt_pos = [[] for _ in wl.ckpt_pos] if args.no_checkpoints else wl.ckpt_pos
+    n_ckpt = sum(len(c) for c in ckpt_pos)
 
     # Initial states: random fp32 ones come with the workload; a "prefix" one
     # is the library's own state after scanning the random prefix from zero,
@@ -108,34 +143,59 @@ def main() -> int:
         init = None
 
     t0 = time.perf_counter()
-    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
+    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, ckpt_pos)
     plan_ms = (time.perf_counter() - t0) * 1e3
+    mfma = plan.info.path == ssm.SSM_PATH_MFMA_BF16
     y = torch.empty_like(inp.x)
-    st = torch.empty((max(wl.n_ckpt, 1), s.nheads, s.headdim, s.d_state), dtype=torch.float32, device=dev)
+    st = torch.empty((max(n_ckpt, 1), s.nheads, s.headdim, s.d_state), dtype=torch.float32, device=dev)
 
     def step():
         ssm.prefill(plan, inp.x, inp.dt, wl.A, inp.B, inp.C, wl.D, init, y_out=y, state_out=st)
 
+    def new_event():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()  # creates the underlying HIP event, whose handle ssm_profile_mark takes
+        return e
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events on the stream the kernels are launched on (torch's current stream)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
+    # HIP events on the stream the kernels are launched on (torch's current stream): start, between the two
+    # kernels of the matrix-core scan (recorded by the library), end
+    ev = [(new_event(), new_event(), new_event()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for a, b in ev:
+    for a, m, b in ev:
         a.record()
+        if mfma:
+            ssm.ssm_profile_mark(m.cuda_event)
         step()
         b.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ssm.ssm_profile_mark(None)
+    call_ms = np.array([a.elapsed_time(b) for a, _, b in ev])
+    scan_ms = np.array([m.elapsed_time(b) for _, m, b in ev]) if mfma else call_ms
+    prep_ms = np.array([a.elapsed_time(m) for a, m, _ in ev]) if mfma else np.zeros_like(call_ms)
     ms_per_step = wall * 1e3 / args.steps
     T = wl.total_tokens
 
-    abytes = algorithmic_bytes(wl)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    kern_ms = float(scan_ms.mean())
+    abytes = algorithmic_bytes(wl, n_ckpt)
     achieved = abytes / (kern_ms * 1e-3) / 1e9
     flops = algorithmic_flops(wl, plan.info.tile_tokens)
+    traffic = None
+    if mfma:
+        m = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(wl.name + ("_nockpt" if args.no_checkpoints else ""))
+        if m:
+            traffic = m["fetch_bytes"] + m["write_bytes"]
     out = {
         "metric": "SSM-layer prefill tokens/s (1 GPU) with state checkpoints",
         "value": T / (ms_per_step * 1e-3),
@@ -151,14 +211,20 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "tokens": T, "batch": wl.batch, "nheads": s.nheads,
                    "headdim": s.headdim, "d_state": s.d_state, "ngroups": s.ngroups, "chunk": s.chunk,
-                   "checkpoints": wl.n_ckpt,
+                   "checkpoints": n_ckpt,
                    "initial_states": 0 if init is None else sum(1 for v in init if v is not None),
-                   "kernel_path": "mfma_bf16" if plan.info.path == 1 else "valu_f32",
-                   "workgroups": plan.info.n_workgroups, "plan_ms": plan_ms},
+                   "kernel_path": "mfma_bf16" if mfma else "valu_f32",
+                   "workgroups": plan.info.n_workgroups, "plan_ms": plan_ms,
+                   "call_ms_mean": float(call_ms.mean()), "call_ms_median": float(np.median(call_ms)),
+                   "call_ms_min": float(call_ms.min())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "ssm_scan_mfma_kernel" if plan.info.path == 1 else "ssm_scan_valu_kernel",
-                     "kernel_ms": kern_ms, "algorithmic_bytes": abytes,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "ssm_scan_mfma_kernel" if mfma else "ssm_scan_valu_kernel",
+                     "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(scan_ms)),
+                     "kernel_ms_min": float(scan_ms.min()),
+                     "prep_kernel": "ssm_prep_kernel" if mfma else None, "prep_kernel_ms": float(prep_ms.mean()),
+                     "algorithmic_bytes": abytes,
+                     "whole_call_frac": abytes / (float(call_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "mfma_tflops_dense_tile": flops / (kern_ms * 1e-3) / 1e12,
                      "mfma_frac": flops / (kern_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }

@@ -244,6 +244,17 @@ int ssm_conv1d_prefill(const ssm_plan_t *plan, int32_t channels, int32_t kernel_
                        const void *const *init_state_ptrs, void *out, void *state_out,
                        int32_t activation, void *hip_stream);
 
+/*
+ * Measurement aid (no passage of the paper: it serves the per-kernel timing of
+ * the benchmark).  ssm_prefill on a matrix-core plan launches two kernels,
+ * the operand preparation and the scan.  With a non-NULL hip_event (a
+ * hipEvent_t created by the caller with timing enabled), every later
+ * ssm_prefill / ssm_prefill_noalloc call of the calling thread records that
+ * event on its stream between the two kernels, so that the caller can time
+ * the scan kernel alone; NULL switches this off again.  Nothing else changes.
+ */
+void ssm_profile_mark(void *hip_event);
+
 /* Release the plan and the device tables it made on first use (Section 4.1's
  * plan lives exactly as long as the batch it describes).  NULL is accepted. */
 void ssm_plan_destroy(ssm_plan_t *plan);

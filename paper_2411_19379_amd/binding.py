@@ -87,6 +87,8 @@ def load_library():
     lib.ssm_conv1d_prefill.restype = ctypes.c_int
     lib.ssm_conv1d_prefill.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.POINTER(vp), vp, vp,
                                        ctypes.c_int32, vp]
+    lib.ssm_profile_mark.restype = None
+    lib.ssm_profile_mark.argtypes = [vp]
     lib.ssm_plan_destroy.restype = None
     lib.ssm_plan_destroy.argtypes = [vp]
     lib.ssm_last_error.restype = ctypes.c_char_p
@@ -141,6 +143,12 @@ def ssm_plan_workspace_bytes(plan: int) -> int:
     n = ctypes.c_size_t()
     _check(load_library().ssm_plan_workspace_bytes(plan, ctypes.byref(n)))
     return n.value
+
+
+def ssm_profile_mark(hip_event: Optional[int]):
+    """Have later prefill calls of this thread record `hip_event` (a raw hipEvent_t, e.g.
+    torch.cuda.Event(...).cuda_event after a first record) between their two kernels; None switches it off."""
+    load_library().ssm_profile_mark(ctypes.c_void_p(hip_event) if hip_event else None)
 
 
 def ssm_plan_destroy(plan: Optional[int]):

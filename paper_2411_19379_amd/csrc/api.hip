@@ -386,6 +386,12 @@ extern "C" int ssm_conv1d_prefill(const ssm_plan_t *plan, int32_t channels, int3
     return SSM_OK;
 }
 
+static thread_local hipEvent_t g_profile_event = nullptr;
+
+hipEvent_t ssm_profile_event() { return g_profile_event; }
+
+extern "C" void ssm_profile_mark(void *hip_event) { g_profile_event = static_cast<hipEvent_t>(hip_event); }
+
 extern "C" void ssm_plan_destroy(ssm_plan_t *plan)
 {
     if (!plan)

@@ -76,6 +76,8 @@ struct ScanArgs {
 // Launchers implemented next to their kernels.
 hipError_t launch_scan_valu(const ssm_plan *plan, const ScanArgs &args, hipStream_t stream);
 hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
+// event to record between the two kernels of the matrix-core scan on the calling thread (nullptr: none)
+hipEvent_t ssm_profile_event();
 bool state_advance_supports(const ssm_shape_t &s);
 hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs,
                                 hipStream_t stream);

@@ -765,9 +765,14 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
     hipLaunchKernelGGL(ssm_prep_kernel, dim3((unsigned)n_tiles * (unsigned)args.G), dim3(kPrepThreads), sizeof(PrepLds),
                        stream, static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C),
                        static_cast<const bf16_t *>(args.dt), args.tiles, frags, dt_t, args.H, args.G, n_tiles);
-    const hipError_t e = hipGetLastError();
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
+    if (hipEvent_t mark = ssm_profile_event()) {
+        e = hipEventRecord(mark, stream);
+        if (e != hipSuccess)
+            return e;
+    }
     switch (args.state_dtype) {
     case SSM_ST_F16: return launch_scan_st<SSM_ST_F16>(plan, args, frags, dt_t, stream);
     case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16>(plan, args, frags, dt_t, stream);

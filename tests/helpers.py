@@ -70,15 +70,17 @@ def oracle_on_heads(wl, heads: Optional[Sequence[int]], init_states, inputs=None
     return ssm_prefill_oracle(x, dt, A, B, C, D, cu, inits, ckpt_pos, want_y=want_y)
 
 
-def gpu_run(wl, init_states, inputs=None, cu=None, ckpt_pos=None, chunk=None):
-    """Run the HIP library on a workload whose tensors live on the GPU."""
+def gpu_run(wl, init_states, inputs=None, cu=None, ckpt_pos=None, chunk=None, state_dtype="f32"):
+    """Run the HIP library on a workload whose tensors live on the GPU.  With a reduced `state_dtype` the initial
+    states must already be tensors of that type, and the checkpoints come back in it."""
     import paper_2411_19379_amd as ssm
 
     s = wl.shape
     inp = inputs if inputs is not None else wl.inputs
     cu = wl.cu_seqlens if cu is None else cu
     ckpt_pos = wl.ckpt_pos if ckpt_pos is None else ckpt_pos
-    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, chunk or s.chunk, s.io_dtype, cu, ckpt_pos)
+    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, chunk or s.chunk, s.io_dtype, cu, ckpt_pos,
+                    state_dtype=state_dtype)
     y, st = ssm.prefill(plan, inp.x, inp.dt, wl.A, inp.B, inp.C, wl.D, init_states)
     torch.cuda.synchronize()
     info = plan.info

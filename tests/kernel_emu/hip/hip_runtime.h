@@ -36,6 +36,8 @@ constexpr hipError_t hipErrorInvalidValue = 1;
 constexpr hipError_t hipErrorInvalidDevice = 101;
 static inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 typedef void *hipStream_t;
+typedef void *hipEvent_t;
+static inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
 constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
 static inline hipError_t hipGetLastError() { return hipSuccess; }

@@ -1,7 +1,7 @@
-"""NOT COLLECTED YET (file name): has not run on a GPU.  The serving loop of test_cache_roundtrip.py with the HIP
-library as the engine: requests resume from fp32 states in device memory under the handles the prefix cache names,
-checkpoint where it asks, and are compared with the oracle's prefill from scratch.  Rename to test_*.py once it has
-passed on an MI355X."""
+"""The serving loop of test_cache_roundtrip.py with the HIP library as the engine (Section 4.1: a request resumes
+from the deepest cached state, checkpoints the branch point the cache asks for and its own last token): states live
+in device memory under the handles the prefix cache names, and every request is compared with the oracle's prefill
+of the whole sequence from scratch."""
 import numpy as np
 import pytest
 import torch

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(ssm_[a-z0-9_]+)\s*\(", header))
     assert names == {"ssm_plan_create", "ssm_plan_info", "ssm_plan_tile", "ssm_plan_workspace_bytes",
                      "ssm_prefill", "ssm_prefill_noalloc", "ssm_state_advance", "ssm_conv1d_prefill",
-                     "ssm_plan_destroy", "ssm_last_error"}
+                     "ssm_profile_mark", "ssm_plan_destroy", "ssm_last_error"}
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in the header but not exported"
 
