@@ -97,6 +97,15 @@ int pc_finish(pc_cache_t *cache, const int32_t *tokens, int32_t m, int32_t hit_l
               int64_t branch_handle, int64_t final_handle, int64_t now, int32_t *n_evicted, int32_t *n_rejected);
 
 /*
+ * A request that pc_begin started and that will not reach pc_finish (it failed
+ * or was cancelled) gives back the pin on its hit state here, so that the state
+ * can be evicted again (Section 4.3: only states no request holds compete for
+ * eviction).  tokens[0..hit_len) is the prefix pc_begin matched; hit_len 0 is
+ * accepted and does nothing.  The tree and the timestamps are not changed.
+ */
+int pc_abort(pc_cache_t *cache, const int32_t *tokens, int32_t hit_len);
+
+/*
  * Handles released by the last pc_finish: the evicted ones in eviction order,
  * then the rejected ones.  Copies them to out[0..) and returns their number,
  * or PC_ERR_BUFFER_TOO_SMALL (the list is kept) if cap is smaller.

@@ -302,7 +302,7 @@ struct pc_cache {
         n->has_state = src->has_state;
         n->handle = src->handle;
         n->last_access = src->last_access;
-        n->pins = src->pins;
+        n->pins = 0;  // pins belong to requests in flight on the original, not to the copy
         if (n->has_state) {
             n->holder_index = (int32_t)holders.size();
             holders.push_back(n);
@@ -444,13 +444,13 @@ static int finish_impl(pc_cache_t *cache, const int32_t *tokens, int32_t m, int3
     cache->released.clear();
     cache->n_evicted_last = 0;
 
+    Node *pinned = nullptr;
     if (hit_len > 0) {
         int32_t matched, in_edge;
         Node *child;
-        Node *h = cache->walk(tokens, hit_len, &matched, &child, &in_edge);
-        if (matched != hit_len || in_edge != 0 || !h->has_state || h->pins <= 0)
+        pinned = cache->walk(tokens, hit_len, &matched, &child, &in_edge);
+        if (matched != hit_len || in_edge != 0 || !pinned->has_state || pinned->pins <= 0)
             return fail(PC_ERR_BAD_REQUEST, "hit_len does not name the pinned state of this sequence");
-        --h->pins;
     }
 
     // the states of this sequence, in the order they were taken: the checkpoint found by speculative insertion (if
@@ -465,6 +465,11 @@ static int finish_impl(pc_cache_t *cache, const int32_t *tokens, int32_t m, int3
     handles.push_back(final_handle);
     std::vector<Node *> at;
     cache->insert(tokens, m, cuts, &at);
+    // The pin goes only now: if the insertion ran out of memory the request still holds its hit state and can
+    // call pc_finish again or give up with pc_abort.  The sequence runs through the hit node, whose path matched
+    // in full, so the insertion never splits an edge above it and the pointer is still that node.
+    if (pinned)
+        --pinned->pins;
 
     std::vector<int64_t> rejected;
     Node *own[2] = {nullptr, nullptr};
@@ -490,6 +495,21 @@ static int finish_impl(pc_cache_t *cache, const int32_t *tokens, int32_t m, int3
     cache->released.insert(cache->released.end(), rejected.begin(), rejected.end());
     *n_evicted = cache->n_evicted_last;
     *n_rejected = (int32_t)rejected.size();
+    return PC_OK;
+}
+
+extern "C" int pc_abort(pc_cache_t *cache, const int32_t *tokens, int32_t hit_len)
+{
+    if (!cache || hit_len < 0 || (hit_len > 0 && !tokens))
+        return fail(PC_ERR_INVALID_ARG, "cache or tokens is NULL, or hit_len is negative");
+    if (hit_len == 0)
+        return PC_OK;  // the request started from nothing: there is no pin to give back
+    int32_t matched, in_edge;
+    Node *child;
+    Node *h = cache->walk(tokens, hit_len, &matched, &child, &in_edge);
+    if (matched != hit_len || in_edge != 0 || !h->has_state || h->pins <= 0)
+        return fail(PC_ERR_BAD_REQUEST, "hit_len does not name the pinned state of this sequence");
+    --h->pins;
     return PC_OK;
 }
 

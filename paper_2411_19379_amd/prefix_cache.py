@@ -57,6 +57,8 @@ def load_library():
         lib.pc_clone.argtypes = [vp, ctypes.POINTER(vp)]
         lib.pc_begin.restype = ctypes.c_int
         lib.pc_begin.argtypes = [vp, i32p, ctypes.c_int32, ctypes.c_int64, ctypes.POINTER(PcLookup)]
+        lib.pc_abort.restype = ctypes.c_int
+        lib.pc_abort.argtypes = [vp, i32p, ctypes.c_int32]
         lib.pc_finish.restype = ctypes.c_int
         lib.pc_finish.argtypes = [vp, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                   ctypes.c_int64, ctypes.c_int64, i32p, i32p]
@@ -122,6 +124,11 @@ class PrefixCache:
         out = PcLookup()
         _check(load_library().pc_begin(self.handle, p, len(a), now, ctypes.byref(out)))
         return out
+
+    def abort(self, tokens: Sequence[int], look: PcLookup) -> None:
+        """Give back the pin of a request that will not reach finish()."""
+        a, p = _tokens(tokens[: look.hit_len] if look.hit_len else [0])
+        _check(load_library().pc_abort(self.handle, p, look.hit_len))
 
     def finish(self, tokens: Sequence[int], look: PcLookup, branch_handle: Optional[int], final_handle: int,
                now: int) -> Tuple[List[int], List[int]]:

@@ -225,3 +225,39 @@ def test_flop_aware_eviction_keeps_long_shared_prefixes():
         c = pc.PrefixCache(capacity_bytes=cap, alpha=alpha, **M7B)
         _, got[alpha] = pc.replay(c, full)
     assert got[2.0] >= 1.5 * got[0.0] and got[2.0] <= best + 1e-12
+
+
+def test_abort_gives_the_pin_back_and_clones_start_unpinned():
+    """A pinned hit state is exempt from eviction (it is what a request in flight resumes from); a request that
+    never finishes must be able to give the pin back, and a snapshot for the alpha search holds no pins."""
+    probe = pc.PrefixCache(capacity_bytes=10 ** 12, alpha=0.0, **M7B)
+    look = probe.begin([1, 2, 3], 1)
+    probe.finish([1, 2, 3, 4], look, None, 100, 1)
+    per_state = probe.stats().used_bytes
+    probe.close()
+
+    tight = pc.PrefixCache(capacity_bytes=int(per_state * 1.5), alpha=0.0, **M7B)   # room for one state
+    look = tight.begin([1, 2, 3], 1)
+    tight.finish([1, 2, 3, 4], look, None, 100, 1)                                 # state 100 after [1,2,3,4]
+    held = tight.begin([1, 2, 3, 4, 9, 9], 2)                                      # a request resumes from it
+    assert held.hit_len == 4 and held.hit_handle == 100
+    copy = tight.clone()                                                           # snapshot while it is pinned
+
+    other = tight.begin([7, 7, 7], 3)
+    ev, _ = tight.finish([7, 7, 7, 7], other, None, 200, 3)
+    assert ev == [], "the pinned state (or the request's own) was evicted"
+    tight.abort([1, 2, 3, 4, 9, 9], held)                                          # the request gives up
+    with pytest.raises(pc.PrefixCacheError) as e:
+        tight.abort([1, 2, 3, 4, 9, 9], held)                                      # the pin is gone
+    assert e.value.code == pc.PC_ERR_BAD_REQUEST
+    other = tight.begin([8, 8, 8], 4)
+    ev, _ = tight.finish([8, 8, 8, 8], other, None, 300, 4)
+    assert sorted(ev) == [100, 200]                                                # both are evictable again
+    tight.abort([5, 5], pc.PcLookup(0, 0, -1))                                     # nothing was pinned: accepted
+    tight.close()
+
+    # the copy took no pin along: its state 100 goes as soon as another state needs the room
+    other = copy.begin([7, 7, 7], 3)
+    ev, _ = copy.finish([7, 7, 7, 7], other, None, 200, 3)
+    assert ev == [100]
+    copy.close()
