@@ -31,13 +31,16 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 / fp16, published
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 # HBM bytes per launch of the scan kernel, from two counter runs of this file
-# (profiles/ssm_scan_mfma_kernel_*_pmc.txt gives the commands and the raw
+# (profiles/ssm_scan_mfma_kernel_cfg3_cfg4_hbm_bytes.txt gives the commands and the raw
 # readings): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each divided by
 # what the same counter reads per KiB actually moved by the 1 GiB copy of
 # --calibrate-copy.  Keyed by the hash of the kernel source the counters were
 # taken on: once that source changes the figure is reported as null.
 MEASURED_TRAFFIC = {
-    # "sha1 of scan_mfma.hip": {"cfg3_7b_32k_bf16": {"fetch_bytes": ..., "write_bytes": ...}},
+    "61d0720a254497c83b693afdd58f86c8c03e3e48": {
+        "cfg3_7b_32k_bf16": {"fetch_bytes": 362366 * 2 * 1024, "write_bytes": 528415 * 1024},
+        "cfg4_7b_128k_ckpt4096_bf16": {"fetch_bytes": 1641357 * 2 * 1024, "write_bytes": 2228322 * 1024},
+    },
 }
 
 

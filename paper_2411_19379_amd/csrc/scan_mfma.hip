@@ -107,11 +107,12 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Global loads of the scan.  They are issued phases ahead of their use; the scheduling fences at the phase ends keep
-// them where they are written.
 // Loads and stores of the tile loop go through buffer descriptors: a wave-uniform base and size in scalar registers,
-// one 32-bit byte offset per lane and a uniform offset, so that no address arithmetic runs on the vector ALUs.  Every
-// access stays inside its descriptor's range; nothing relies on what the hardware does beyond it.
+// one 32-bit byte offset per lane and a uniform offset, so that no address arithmetic runs on the vector ALUs.  The
+// loads are issued phases ahead of their use; the scheduling fences at the phase ends keep them where they are
+// written.  Every access stays inside its descriptor's range.  The one use of the hardware's range check is a
+// descriptor of size zero, through which a wave that has no next tile issues its look-ahead loads: they return
+// zeros without touching memory (and their base address is valid memory in any case).
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
