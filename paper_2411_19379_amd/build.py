@@ -41,6 +41,20 @@ def build_prefix_cache(verbose: bool = False) -> str:
     return CACHE_LIB_PATH
 
 
+PEAK_PROBE_PATH = os.path.join(_PKG, "peak_probe")
+
+
+def build_peak_probe(verbose: bool = False) -> str:
+    """Stand-alone measurement of what the GPU sustains on a streaming copy and on dense MFMA loops."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-o", PEAK_PROBE_PATH, os.path.join(CSRC, "peak_probe.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PEAK_PROBE_PATH
+
+
 if __name__ == "__main__":
     build_library(verbose=True)
     build_prefix_cache(verbose=True)
+    build_peak_probe(verbose=True)
