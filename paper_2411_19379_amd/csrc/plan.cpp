@@ -160,6 +160,17 @@ extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
         }
         plan->seqs[i].tile_end = (int32_t)plan->tiles.size();
     }
+    if (plan->path == SSM_PATH_MFMA_BF16 && s.headdim % kMfmaWideChannels == 0) {
+        // The matrix-core scan has a variant whose workgroups own 64 channels of a head instead of 32: one set of
+        // operand loads serves twice the rows, at half the number of workgroups.  It pays as soon as those still
+        // fill the GPU.
+        int64_t streams = 0;
+        for (int32_t i = 0; i < batch; ++i)
+            streams += cu_seqlens_host[i + 1] > cu_seqlens_host[i];
+        streams *= (int64_t)s.nheads * (s.headdim / kMfmaWideChannels);
+        if (streams >= kMfmaWideMinWorkgroups)
+            plan->p_split = s.headdim / kMfmaWideChannels;
+    }
     const int64_t wgs = (int64_t)batch * s.nheads * plan->p_split;
     if (wgs > 0x7fffffffLL) {
         delete plan;

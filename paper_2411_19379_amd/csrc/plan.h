@@ -58,3 +58,8 @@ constexpr int kMfmaTileTokens = 64;
 // register images, 16 KiB each, and the raw score blocks, 6 KiB), then per (tile, head) the tile's dt, 64 bf16.
 constexpr size_t kMfmaTileGroupBytes = 38912;
 constexpr size_t kMfmaDtBytes = 128;
+
+// The wide variant of the matrix-core scan (64 channels of a head per workgroup instead of 32) is chosen when it
+// still has at least this many workgroups with work: one per compute unit of the GPU this library is written for.
+constexpr int kMfmaWideChannels = 64;
+constexpr int kMfmaWideMinWorkgroups = 256;

@@ -388,8 +388,8 @@ __device__ __forceinline__ void pack_scores(const float (&v)[16], uint4 &g0, uin
 //   FAST: e^{l_i-l_j} dt_j = e^{l_i-l_31} * e^{l_31-l_j} dt_j from the two factor tables; the caller has checked that
 //         the decay over the whole tile stays inside the fp32 exponent range, so neither factor over- or underflows.
 //   else: one exponential of l_i - l_j per entry; no factor can overflow whatever the decay.
-template <bool FAST>
-__device__ __forceinline__ void mask_diag(const uint4 &raw0, const uint4 &raw1, const WaveLds &tb, int off, int i, int q,
+template <bool FAST, typename Tables>
+__device__ __forceinline__ void mask_diag(const uint4 &raw0, const uint4 &raw1, const Tables &tb, int off, int i, int q,
                                           float Dh, uint4 &g0, uint4 &g1)
 {
     float v[16];
@@ -726,12 +726,355 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     SSM_TRACE_FLUSH
 }
 
+// ================================================================ the scan, 64 channels per workgroup
+// Same algebra and the same hand-off as ssm_scan_mfma_kernel, but a wave's tile covers 64 channels (two halves of 32)
+// of its head, so that one set of operand loads (B^T, C, raw scores: 38 KiB per tile) serves twice the rows.  What
+// limits the scan is the rate at which a CU can pull operands through its L1; this variant needs 54 KiB per 64
+// channels and tile instead of 2 x 47 KiB.  It has half as many workgroups, so it is the better choice only when
+// those still fill the GPU.  To fit the registers it streams the blocks of 32 state indices: the B^T operand, the
+// tile-local state, the hand-off and S.C of one block at a time, the intra-tile term last, added onto
+// e^{l_i} (S C_i) in the same accumulators.
+constexpr int kPW64 = 64;
+constexpr int LDX64 = kPW64 + 8;  // row stride of the x / y tile of a wave (elements): 144 bytes
+
+struct Wave64Lds {                 // private to one wave
+    bf16_t XY[kQ][LDX64];          // x of the tile as loaded, token major; later y on its way to coalesced stores
+    float ell2[kQ], cj[kQ], ei[kQ], wt[kQ], ri[kQ], cf[kQ];  // as in WaveLds
+};
+
+struct Lds64 {
+    float4 S[2][4][4][64];         // the running state: [channel half][block of 32 n][element group a][lane]
+    int done[4];                   // per block of 32 n: how many tiles of the sequence have left their state in it
+    int pad[12];
+    Wave64Lds wv[kWaves];
+};
+
 template <int ST>
+__global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
+    const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
+    void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
+    const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
+    int G, int p_split, int wg_per_xcd, int n_wg)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    Lds64 &L = *reinterpret_cast<Lds64 *>(lds_raw);
+
+    const int wg = (blockIdx.x & 7) * wg_per_xcd + (blockIdx.x >> 3);  // same renumbering as the 32-channel kernel
+    if (wg >= n_wg)
+        return;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const int ps = wg % p_split;
+    const int h = (wg / p_split) % H;
+    const int seq = wg / (p_split * H);
+    const int g = h / (H / G);
+    const int pbase = ps * kPW64;
+    const float Ah = A_[h], Dh = D_[h];
+    const void *init = init_ptrs ? init_ptrs[seq] : nullptr;
+    const SsmSeq sq = seqs[seq];
+    const int tile_begin = sq.tile_begin;
+    const int n_tiles = sq.tile_end - sq.tile_begin;
+    if (n_tiles <= 0)
+        return;  // empty sequence: the whole workgroup leaves before any barrier
+
+    Wave64Lds &W = L.wv[w];
+    const int i = lane & 31, q = lane >> 5;
+    const int g4 = lane >> 4;
+    const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
+    const int tr_row_nat = 8 * (g4 >> 1) + ((lane & 15) >> 2);  // tokens 16 ks + 8 q + e (state update)
+    const int tr_row_sc = 4 * (g4 >> 1) + ((lane & 15) >> 2);   // tokens 8 (e/4) + 4 q + e%4 (score order)
+    const int tok_l = lane >> 3, xcol = 8 * (lane & 7);          // x / y rows: 8 lanes x 16 bytes per 128-byte row
+    // + 32 c kN (channel half) + 32 nb + 8 a: this lane's 4 state values
+    const size_t state_row = ((size_t)h * P + pbase + i) * kN + 4 * q;
+    const uint32_t xrow_b = (uint32_t)H * P * 2;                         // bytes per token row of x and y
+    const unsigned char *xh = reinterpret_cast<const unsigned char *>(x) + ((size_t)h * P + pbase) * 2;  // uniform
+    unsigned char *yh = reinterpret_cast<unsigned char *>(y) + ((size_t)h * P + pbase) * 2;
+    const uint32_t xoff_lane = tok_l * xrow_b + xcol * 2;               // row tok_l, this lane's 16 bytes
+    const uint32_t lane16 = lane * 16;
+
+    // The state the sequence starts from (its cached state or zero) goes into LDS the way a tile would have left it.
+    for (int blk = w; blk < 32; blk += kWaves) {
+        const int c = blk >> 4, nb = (blk >> 2) & 3, a = blk & 3;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (init)
+            v = load_state4(init, state_row + (size_t)32 * c * kN + 32 * nb + 8 * a, ST);
+        L.S[c][nb][a][lane] = v;
+    }
+    if (threadIdx.x < 4)
+        L.done[threadIdx.x] = 0;
+    lds_barrier();  // the only workgroup barrier: the starting state and the counters are in place
+    constexpr uint32_t kBfOff = kCfWords * 16, kCbOff = (kCfWords + kBfWords) * 16;
+    const unsigned char *img_g = reinterpret_cast<const unsigned char *>(frags) + (size_t)g * kMfmaTileGroupBytes;
+
+    // dt and x of a tile are loaded one tile of this wave ahead (before the epilogue of the current one).  Rows past
+    // the end of a partial tile re-read the tile's last row: their weights are zero, so any finite value will do.
+    // After its last tile the wave issues these loads once more through descriptors of size zero (on the current
+    // tile's addresses): they return zeros without touching memory, and the loop needs no second copy of its tail.
+    uint32_t dt_raw = 0;
+    uint4 xr[8];
+    auto issue_first_loads = [&](int tile_idx, const SsmTile &tl, bool live) {
+        const rsrc_t dtr = make_rsrc(dt_t + ((size_t)tile_idx * H + h) * kQ, live ? kQ * 2 : 0);
+        dt_raw = __builtin_amdgcn_raw_buffer_load_b16(dtr, lane * 2, 0, 0);
+        const rsrc_t xrs =
+            make_rsrc(xh + (size_t)tl.tok0 * xrow_b, live ? (uint32_t)(tl.len - 1) * xrow_b + kPW64 * 2 : 0);
+        if (tl.len == kQ) {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                xr[kk] = buf_load16(xrs, xoff_lane, (uint32_t)(8 * kk) * xrow_b);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int tok = tok_l + 8 * kk < tl.len ? tok_l + 8 * kk : tl.len - 1;
+                xr[kk] = buf_load16(xrs, (uint32_t)tok * xrow_b + xcol * 2, 0);
+            }
+        }
+    };
+    if (w >= n_tiles)
+        return;  // a wave without tiles; no barrier follows
+    int tile_idx = __builtin_amdgcn_readfirstlane(tile_begin + w);
+    SsmTile t = tiles[tile_idx], t_next = t;
+    issue_first_loads(tile_idx, t, true);
+    for (int k = w; k < n_tiles; k += kWaves) {  // this wave's tiles
+        __builtin_amdgcn_sched_barrier(0);
+        const rsrc_t img = make_rsrc(img_g + (size_t)tile_idx * G * kMfmaTileGroupBytes, kMfmaTileGroupBytes);
+        // B^T and C for one block of 32 state indices
+        uint4 bfb[4], cfr[2][2];
+        auto load_b = [&](int nb) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                bfb[ks] = buf_load16(img, lane16, kBfOff + (nb * 4 + ks) * 1024);
+        };
+        auto load_c = [&](int nb) {
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+                    cfr[ih][hf] = buf_load16(img, lane16, (ih * 8 + 2 * nb + hf) * 1024);
+        };
+        load_b(0);
+        load_c(0);
+        phase_end();
+
+        // ---------------- factor tables, x into LDS, decay-weighted x of both channel halves as fp16 operands
+        float dl;
+        bool fast;
+        {
+            const float dtj = __uint_as_float(dt_raw << 16);
+            const float ell2 = wave_inclusive_sum(dtj * Ah) * kLog2e;
+            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
+            dl = exp2_fast(last);   // padded tokens have dt = 0, so this is e^{l_len}
+            fast = last > -100.f;   // 2^+-100 is far inside the fp32 range: the two-factor form of the decay is safe
+            W.ell2[lane] = ell2;
+            W.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
+            W.ei[lane] = exp2_fast(ell2);
+            W.wt[lane] = exp2_fast(last - ell2) * dtj;
+            W.ri[lane] = exp2_fast(ell2 - e31);
+            W.cf[lane] = exp2_fast(e31 - ell2) * dtj;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                *reinterpret_cast<uint4 *>(&W.XY[tok_l + 8 * kk][xcol]) = xr[kk];
+        }
+        lds_wait();
+        uint4 xw[2][4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16_t *px = &W.XY[tr_row_nat][32 * c + tr_col];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const uint4 xv = lds_frag_tr(px + 16 * ks * LDX64, px + (16 * ks + 4) * LDX64);
+                const float4 w0 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q]);
+                const float4 w1 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q + 4]);
+                xw[c][ks] = make_uint4(pack2_f16(w0.x * bf16_lo(xv.x), w0.y * bf16_hi(xv.x)),
+                                       pack2_f16(w0.z * bf16_lo(xv.y), w0.w * bf16_hi(xv.y)),
+                                       pack2_f16(w1.x * bf16_lo(xv.z), w1.y * bf16_hi(xv.z)),
+                                       pack2_f16(w1.z * bf16_lo(xv.w), w1.w * bf16_hi(xv.w)));
+            }
+        }
+        const bool more = k + kWaves < n_tiles;
+        if (more)  // the descriptor of this wave's next tile
+            t_next = tiles[tile_idx + kWaves];
+        phase_end();
+
+        // ---------------- per block of 32 state indices: tile-local state, hand-off, S.C
+        f32x16 Yo[2][2];  // [channel half][token half]
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+                Yo[c][ih] = zero16();
+        auto block = [&](int nb) {
+            f32x16 Sl[2];
+            Sl[0] = zero16();
+            Sl[1] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                Sl[0] = mfma_f16(bfb[ks], xw[0][ks], Sl[0]);
+                Sl[1] = mfma_f16(bfb[ks], xw[1][ks], Sl[1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (nb < 3)
+                load_b(nb + 1);  // into the registers the MFMAs above have just read
+            // S as it was before this tile comes from LDS, where the wave of the previous tile left the block; this
+            // tile's S goes back in its place.  The value read also feeds S.C.
+            wait_counter(&L.done[nb], k);
+            uint4 s16[2][2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                float4 sp[4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    sp[a] = L.S[c][nb][a][lane];
+                float4 sn[4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    sn[a] = make_float4(__builtin_fmaf(dl, sp[a].x, Sl[c][4 * a + 0]), __builtin_fmaf(dl, sp[a].y, Sl[c][4 * a + 1]),
+                                        __builtin_fmaf(dl, sp[a].z, Sl[c][4 * a + 2]), __builtin_fmaf(dl, sp[a].w, Sl[c][4 * a + 3]));
+                    L.S[c][nb][a][lane] = sn[a];
+                }
+                if (t.ckpt_slot >= 0) {
+                    const size_t slot_row = (size_t)t.ckpt_slot * H * P * kN + state_row + (size_t)32 * c * kN + 32 * nb;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+                        store_state4(state_out, slot_row + 8 * a, sn[a], ST);
+                }
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+                    s16[c][hf] = make_uint4(pack2_f16(sp[2 * hf].x, sp[2 * hf].y), pack2_f16(sp[2 * hf].z, sp[2 * hf].w),
+                                            pack2_f16(sp[2 * hf + 1].x, sp[2 * hf + 1].y),
+                                            pack2_f16(sp[2 * hf + 1].z, sp[2 * hf + 1].w));
+            }
+            publish_counter(&L.done[nb], k + 1, lane);
+            // S_s C_i over the 32 state indices of this block: two k-steps of 16
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    Yo[c][0] = mfma_f16(s16[c][hf], cfr[0][hf], Yo[c][0]);
+                    Yo[c][1] = mfma_f16(s16[c][hf], cfr[1][hf], Yo[c][1]);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            if (nb < 3)
+                load_c(nb + 1);
+        };
+        block(0);
+        block(1);
+        phase_end();
+        block(2);
+        block(3);
+        phase_end();
+
+        // ---------------- the intra-tile term, added onto e^{l_i} (S C_i) in the same accumulators: raw scores,
+        // decay mask (+ D on the diagonal), x in score order, Gm.x
+        uint4 cb[3][2];
+#pragma unroll
+        for (int blk = 0; blk < 3; ++blk)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                cb[blk][hf] = buf_load16(img, lane16, kCbOff + (blk * 2 + hf) * 1024);
+        phase_end();
+#pragma unroll
+        for (int ih = 0; ih < 2; ++ih) {
+            const float ei = W.ei[32 * ih + i];
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Yo[c][ih][r] *= ei;
+        }
+        {
+            uint4 gd[2][2], go[2];
+            if (fast) {
+                mask_diag<true>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
+                mask_diag<true>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
+            } else {
+                mask_diag<false>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
+                mask_diag<false>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
+            }
+            {
+                // off-diagonal block (keys 0..31, queries 32..63): unmasked, and both factors of
+                // e^{l_i-l_31} * e^{l_31-l_j} dt_j are <= 1 whatever the decay
+                float v[16];
+                unpack_scores(cb[2][0], cb[2][1], v);
+                const float ri = W.ri[32 + i];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float4 f4 = *reinterpret_cast<const float4 *>(&W.cf[8 * a + 4 * q]);
+                    v[4 * a + 0] *= ri * f4.x;
+                    v[4 * a + 1] *= ri * f4.y;
+                    v[4 * a + 2] *= ri * f4.z;
+                    v[4 * a + 3] *= ri * f4.w;
+                }
+                pack_scores(v, go[0], go[1]);
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                uint4 xs[2][2];  // x^T of each token half, tokens in the order of the score blocks' rows
+#pragma unroll
+                for (int ih = 0; ih < 2; ++ih) {
+                    const bf16_t *px = &W.XY[32 * ih + tr_row_sc][32 * c + tr_col];
+                    xs[ih][0] = lds_frag_tr(px, px + 8 * LDX64);
+                    xs[ih][1] = lds_frag_tr(px + 16 * LDX64, px + 24 * LDX64);
+                }
+                Yo[c][0] = mfma_bf16(xs[0][0], gd[0][0], Yo[c][0]);
+                Yo[c][1] = mfma_bf16(xs[1][0], gd[1][0], Yo[c][1]);
+                Yo[c][0] = mfma_bf16(xs[0][1], gd[0][1], Yo[c][0]);
+                Yo[c][1] = mfma_bf16(xs[1][1], gd[1][1], Yo[c][1]);
+                Yo[c][1] = mfma_bf16(xs[0][0], go[0], Yo[c][1]);
+                Yo[c][1] = mfma_bf16(xs[0][1], go[1], Yo[c][1]);
+            }
+        }
+        phase_end();
+        // the first loads of this wave's next tile, in flight under the epilogue
+        issue_first_loads(more ? tile_idx + kWaves : tile_idx, t_next, more);
+        phase_end();
+        // y on its way to LDS, over the x tile (every read of it has been issued, and LDS runs a wave's accesses in
+        // order).  Y^T[p, i]: element r of this lane is channel 32 c + 8(r/4) + 4q + r%4 of token 32 ih + i
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int ih = 0; ih < 2; ++ih)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    *reinterpret_cast<uint2 *>(&W.XY[32 * ih + i][32 * c + 8 * a + 4 * q]) =
+                        make_uint2(pack2_bf16(Yo[c][ih][4 * a + 0], Yo[c][ih][4 * a + 1]),
+                                   pack2_bf16(Yo[c][ih][4 * a + 2], Yo[c][ih][4 * a + 3]));
+        lds_wait();
+
+        // ---------------- y from LDS to device memory in whole 128-byte rows
+        {
+            const rsrc_t yrs = make_rsrc(yh + (size_t)t.tok0 * xrow_b, (uint32_t)(t.len - 1) * xrow_b + kPW64 * 2);
+            if (t.len == kQ) {  // full tile: no predication
+#pragma unroll
+                for (int m = 0; m < 8; ++m)
+                    buf_store16(yrs, xoff_lane, (uint32_t)(8 * m) * xrow_b,
+                                *reinterpret_cast<const uint4 *>(&W.XY[tok_l + 8 * m][xcol]));
+            } else {
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const int tok = tok_l + 8 * m;
+                    if (tok < t.len)
+                        buf_store16(yrs, xoff_lane, (uint32_t)(8 * m) * xrow_b,
+                                    *reinterpret_cast<const uint4 *>(&W.XY[tok][xcol]));
+                }
+            }
+        }
+        phase_end();
+        t = t_next;
+        tile_idx += kWaves;
+    }
+}
+
+// WIDE: 64 channels per workgroup instead of 32.
+template <int ST, bool WIDE>
 hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
                           hipStream_t stream)
 {
     static std::once_flag attr_once[64];
     static hipError_t attr_err[64];
+    constexpr size_t lds = WIDE ? sizeof(Lds64) : sizeof(Lds);
+    const void *kernel = WIDE ? reinterpret_cast<const void *>(ssm_scan_mfma64_kernel<ST>)
+                              : reinterpret_cast<const void *>(ssm_scan_mfma_kernel<ST>);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
@@ -739,18 +1082,34 @@ hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     std::call_once(attr_once[dev], [&]() {
-        attr_err[dev] = hipFuncSetAttribute(reinterpret_cast<const void *>(ssm_scan_mfma_kernel<ST>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Lds));
+        attr_err[dev] = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err[dev] != hipSuccess)
         return attr_err[dev];
     const int n_wg = plan->n_workgroups;
     const int per_xcd = (n_wg + 7) / 8;
-    hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), sizeof(Lds), stream,
-                       static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y), args.state_out,
-                       args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G, args.p_split, per_xcd,
-                       n_wg);
+    if (WIDE)
+        hipLaunchKernelGGL((ssm_scan_mfma64_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
+                           static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
+                           args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
+                           args.p_split, per_xcd, n_wg);
+    else
+        hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
+                           static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
+                           args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
+                           args.p_split, per_xcd, n_wg);
     return hipGetLastError();
+}
+
+template <bool WIDE>
+hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
+                             hipStream_t stream)
+{
+    switch (args.state_dtype) {
+    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16, WIDE>(plan, args, frags, dt_t, stream);
+    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16, WIDE>(plan, args, frags, dt_t, stream);
+    default: return launch_scan_st<SSM_ST_F32, WIDE>(plan, args, frags, dt_t, stream);
+    }
 }
 
 }  // namespace
@@ -774,9 +1133,7 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
         if (e != hipSuccess)
             return e;
     }
-    switch (args.state_dtype) {
-    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16>(plan, args, frags, dt_t, stream);
-    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16>(plan, args, frags, dt_t, stream);
-    default: return launch_scan_st<SSM_ST_F32>(plan, args, frags, dt_t, stream);
-    }
+    if (args.P / args.p_split == kPW64)
+        return launch_scan_width<true>(plan, args, frags, dt_t, stream);
+    return launch_scan_width<false>(plan, args, frags, dt_t, stream);
 }

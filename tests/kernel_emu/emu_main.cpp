@@ -7,6 +7,7 @@
 //   a 6th argument "advance" runs the roll-forward kernel instead of the scan: every sequence's state (its initial
 //   state, or zeros) is advanced in place, and the output holds y and then one state per sequence;
 //   a 7th argument f16 or bf16 keeps cached states in that type (converted from and to fp32 around the run)
+//   with EMU_WIDE set in the environment the matrix-core scan runs in its 64-channel variant
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -99,6 +100,11 @@ int main(int argc, char **argv)
     if (rc != 0) {
         fprintf(stderr, "ssm_plan_create: %d %s\n", rc, ssm_last_error());
         return 2;
+    }
+    if (getenv("EMU_WIDE") && plan->path == SSM_PATH_MFMA_BF16 && P % kMfmaWideChannels == 0) {
+        // the 64-channel variant of the matrix-core scan, which the plan itself picks only for grids that fill a GPU
+        plan->p_split = P / kMfmaWideChannels;
+        plan->n_workgroups = batch * H * plan->p_split;
     }
     const size_t nt = plan->tiles.size();
     SsmTile *tiles = static_cast<SsmTile *>(guarded(sizeof(SsmTile) * (nt ? nt : 1), end_aligned));

@@ -151,8 +151,8 @@ def _read_result(path, wl, n_states=None):
     return y.reshape(wl.total_tokens, s.nheads, s.headdim), st, raw
 
 
-def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False, state_type=None):
-    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}_{state_type}.bin")
+def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False, state_type=None, wide=False):
+    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}_{state_type}_{wide}.bin")
     if not os.path.exists(pin):
         _write_problem(pin, wl, init)
     cmd = [binary, pin, pout, str(order), align]
@@ -162,7 +162,8 @@ def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False,
         cmd.append("advance" if advance else "scan")
         if state_type:
             cmd.append(state_type)
-    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    env = dict(os.environ, EMU_WIDE="1") if wide else None  # the 64-channel variant of the matrix-core scan
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300, env=env)
     assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
     return _read_result(pout, wl, n_states=wl.batch if advance else None)
 
@@ -201,7 +202,7 @@ CASES = {
 }
 
 
-def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None):
+def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None, wide=False):
     (H, P, N, G, chunk), cfg, kw = CASES[case]
     if io == "f32" and P * N > 8192:
         pytest.skip("the fp32 vector kernel holds at most 8192 state elements per head")
@@ -213,7 +214,7 @@ def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None):
     y_ref, st_ref = _oracle(wl, init)
     first = None
     for order, align in ((0, "end"), (1, "start"), (7, "end"), (12, "start")):
-        y, st, raw = _emulate(binary, wl, init, tmp_path, order, align)
+        y, st, raw = _emulate(binary, wl, init, tmp_path, order, align, wide=wide)
         assert np.all(np.isfinite(y)) and np.all(np.isfinite(st)), "an output was never written, or LDS was read before written"
         assert max(rel_err(y, y_ref)) <= (y_tol or TOL[io])
         assert max(rel_err(st.astype(np.float64), st_ref)) <= (state_tol or TOL[io])
@@ -391,6 +392,13 @@ def test_full_size_spot_check(tmp_path_factory):
 @pytest.mark.parametrize("case", sorted(CASES))
 def test_emulated_8wave_scan_matches_oracle_in_any_wave_order(emu_binary_8waves, tmp_path, case):
     _check_case(emu_binary_8waves, tmp_path, "bf16", case)
+
+
+@pytest.mark.parametrize("case", ["ragged", "long", "tiny", "p128", "empty_seq"])
+def test_emulated_64_channel_scan_matches_oracle_in_any_wave_order(emu_binary, tmp_path, case):
+    """The variant of the matrix-core scan whose workgroups own 64 channels (the plan picks it for grids that fill a
+    GPU; the emulation driver forces it): same checks as for the 32-channel kernel."""
+    _check_case(emu_binary, tmp_path, "bf16", case, wide=True)
 
 
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
