@@ -95,7 +95,7 @@ def emu_binary(tmp_path_factory):
 
 
 @pytest.fixture(scope="session")
-def emu_binary_8waves(tmp_path_factory):
+def emu_binary_4waves(tmp_path_factory):
     """The matrix-core scan with 4 waves per workgroup instead of the shipped 8."""
     return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4"])
 
@@ -390,8 +390,8 @@ def test_full_size_spot_check(tmp_path_factory):
 
 
 @pytest.mark.parametrize("case", sorted(CASES))
-def test_emulated_8wave_scan_matches_oracle_in_any_wave_order(emu_binary_8waves, tmp_path, case):
-    _check_case(emu_binary_8waves, tmp_path, "bf16", case)
+def test_emulated_4wave_scan_matches_oracle_in_any_wave_order(emu_binary_4waves, tmp_path, case):
+    _check_case(emu_binary_4waves, tmp_path, "bf16", case)
 
 
 @pytest.mark.parametrize("case", ["ragged", "long", "tiny", "p128", "empty_seq"])
