@@ -43,6 +43,8 @@ struct Lane {
     ucontext_t ctx;
     void *stack = nullptr;
     Idx tid{0, 0, 0};
+    Idx bid{0, 0, 0};              // the workgroup this lane belongs to
+    unsigned char *lds = nullptr;  // and that workgroup's LDS
     St st = RUN;
     Coll k;
     int barrier_line = 0;
@@ -53,8 +55,7 @@ constexpr size_t kStack = 256 * 1024;
 std::vector<Lane> lanes;
 Lane *cur = nullptr;
 ucontext_t sched_ctx;
-Idx g_block{0, 0, 0};
-unsigned char *g_lds = nullptr;
+bool g_cooperative = false;  // run all workgroups of a launch at once (kernels whose workgroups wait for each other)
 void (*g_fn)(void *) = nullptr;
 void *g_arg = nullptr;
 int g_order_mode = 0;  // 0 forward, 1 reverse, >=2 shuffle with this seed
@@ -65,7 +66,7 @@ int g_launch_index = 0;
 
 [[noreturn]] void die(const char *msg, int a = 0, int b = 0)
 {
-    fprintf(stderr, "EMU ERROR: %s (%d, %d) block %u\n", msg, a, b, g_block.x);
+    fprintf(stderr, "EMU ERROR: %s (%d, %d) block %u\n", msg, a, b, cur ? cur->bid.x : 0u);
     fflush(stderr);
     _exit(3);
 }
@@ -250,9 +251,9 @@ void run_collective(Lane *L)
 
 // run one wave until all its lanes sit at a barrier, are done, or have yielded (a spin-wait gives the other waves a
 // turn); returns true in the last case
-bool run_wave(int w, int n_lanes)
+bool run_wave(int lane0, int w, int n_lanes)
 {
-    Lane *L = &lanes[64 * w];
+    Lane *L = &lanes[lane0 + 64 * w];
     const int nl = std::min(64, n_lanes - 64 * w);
     for (;;) {
         bool progressed = false;
@@ -298,26 +299,47 @@ bool run_wave(int w, int n_lanes)
     }
 }
 
-void run_block(dim3 block)
+// Runs a set of workgroups to completion, all of them resident at once (one workgroup in the ordinary case).  The
+// waves of all of them take turns in the chosen order; a barrier releases the lanes of its own workgroup only.
+void run_blocks(const std::vector<unsigned> &ids, dim3 grid, dim3 block, size_t lds_bytes)
 {
-    const int n_lanes = (int)(block.x * block.y * block.z);
-    const int n_waves = (n_lanes + 63) / 64;
-    lanes.assign(n_lanes, Lane());
-    for (int t = 0; t < n_lanes; ++t) {
-        Lane &ln = lanes[t];
-        ln.stack = mmap(nullptr, kStack, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS | MAP_NORESERVE, -1, 0);
-        if (ln.stack == MAP_FAILED)
-            die("mmap of a lane stack failed");
-        ln.tid = Idx{(unsigned)t % block.x, ((unsigned)t / block.x) % block.y, (unsigned)t / (block.x * block.y)};
-        getcontext(&ln.ctx);
-        ln.ctx.uc_stack.ss_sp = ln.stack;
-        ln.ctx.uc_stack.ss_size = kStack;
-        ln.ctx.uc_link = nullptr;
-        makecontext(&ln.ctx, trampoline, 0);
+    const int n_per = (int)(block.x * block.y * block.z);
+    const int waves_per = (n_per + 63) / 64;
+    const int n_blocks = (int)ids.size();
+    // LDS of each workgroup: exactly lds_bytes, flush against an inaccessible page, filled with NaN patterns
+    const size_t page = 4096, span = (lds_bytes + page - 1) / page * page;
+    std::vector<unsigned char *> maps(n_blocks);
+    lanes.assign((size_t)n_blocks * n_per, Lane());
+    for (int bi = 0; bi < n_blocks; ++bi) {
+        unsigned char *m = static_cast<unsigned char *>(
+            mmap(nullptr, span + 2 * page, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0));
+        if (m == MAP_FAILED)
+            die("mmap of LDS failed");
+        mprotect(m, page, PROT_NONE);
+        mprotect(m + page + span, page, PROT_NONE);
+        maps[bi] = m;
+        unsigned char *lds = m + page + span - ((lds_bytes + 15) / 16 * 16);
+        memset(lds, 0xFF, (lds_bytes + 15) / 16 * 16);
+        const unsigned b = ids[bi];
+        for (int t = 0; t < n_per; ++t) {
+            Lane &ln = lanes[(size_t)bi * n_per + t];
+            ln.stack = mmap(nullptr, kStack, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS | MAP_NORESERVE, -1, 0);
+            if (ln.stack == MAP_FAILED)
+                die("mmap of a lane stack failed");
+            ln.tid = Idx{(unsigned)t % block.x, ((unsigned)t / block.x) % block.y, (unsigned)t / (block.x * block.y)};
+            ln.bid = Idx{b % grid.x, (b / grid.x) % grid.y, b / (grid.x * grid.y)};
+            ln.lds = lds;
+            getcontext(&ln.ctx);
+            ln.ctx.uc_stack.ss_sp = ln.stack;
+            ln.ctx.uc_stack.ss_size = kStack;
+            ln.ctx.uc_link = nullptr;
+            makecontext(&ln.ctx, trampoline, 0);
+        }
     }
+    const int n_waves = n_blocks * waves_per;
     std::vector<int> order(n_waves);
-    std::mt19937 rng((unsigned)g_order_mode * 7919u + g_block.x);
-    long epoch = 0, yield_passes = 0;
+    std::mt19937 rng((unsigned)g_order_mode * 7919u + ids[0] % grid.x);
+    long yield_passes = 0;
     for (;;) {
         for (int w = 0; w < n_waves; ++w)
             order[w] = g_order_mode == 1 ? n_waves - 1 - w : w;
@@ -325,40 +347,52 @@ void run_block(dim3 block)
             std::shuffle(order.begin(), order.end(), rng);
         bool yielded = false;
         for (int w : order)
-            yielded = run_wave(w, n_lanes) || yielded;
-        if (yielded) {  // a wave is spinning on something another wave will write: give everybody another turn
-            if (++yield_passes > 50000000L)
+            yielded = run_wave((w / waves_per) * n_per, w % waves_per, n_per) || yielded;
+        // barriers, workgroup by workgroup
+        bool released = false, any_waiting = false;
+        for (int bi = 0; bi < n_blocks; ++bi) {
+            int n_bar = 0, n_done = 0, n_other = 0;
+            for (int t = 0; t < n_per; ++t) {
+                const St st = lanes[(size_t)bi * n_per + t].st;
+                n_bar += st == W_BARRIER;
+                n_done += st == DONE;
+                n_other += st != W_BARRIER && st != DONE;
+            }
+            if (n_bar == 0)
+                continue;
+            any_waiting = true;
+            if (n_other != 0)
+                continue;  // some of its waves have only yielded: they get there in a later pass
+            if (n_done != 0) {
+                cur = &lanes[(size_t)bi * n_per];
+                die("barrier reached by only part of the workgroup: the rest has exited (a hang on the GPU)", n_bar, n_done);
+            }
+            for (int t = 0; t < n_per; ++t)
+                lanes[(size_t)bi * n_per + t].st = RUN;
+            released = true;
+        }
+        if (yielded || released) {  // a wave is spinning on something another wave will write, or a barrier opened
+            if (yielded && ++yield_passes > 50000000L)
                 die("waves keep yielding: a spin-wait that nothing ends (a hang on the GPU)");
             continue;
         }
-        int n_bar = 0, n_done = 0, line = -1;
-        for (Lane &ln : lanes) {
-            if (ln.st == W_BARRIER) {
-                ++n_bar;
-                if (line < 0)
-                    line = ln.barrier_line;
-            } else {
-                ++n_done;
-            }
-        }
-        if (n_bar == 0)
-            break;
-        if (n_done != 0)
-            die("barrier reached by only part of the workgroup: the rest has exited (a hang on the GPU)", n_bar, n_done);
-        (void)line;  // waves may legitimately meet at different source lines of the same barrier count
-        for (Lane &ln : lanes)
-            ln.st = RUN;
-        ++epoch;
+        if (any_waiting)
+            die("waves wait at a barrier that cannot open");
+        break;  // every lane is done
     }
     for (Lane &ln : lanes)
         munmap(ln.stack, kStack);
     lanes.clear();
+    cur = nullptr;
+    for (unsigned char *m : maps)
+        munmap(m, span + 2 * page);
 }
 }  // namespace
 
 Idx &thread_idx() { return cur->tid; }
-Idx &block_idx() { return g_block; }
-unsigned char *lds_base() { return g_lds; }
+Idx &block_idx() { return cur->bid; }
+unsigned char *lds_base() { return cur->lds; }
+void set_cooperative(bool on) { g_cooperative = on; }
 void set_order_mode(int m) { g_order_mode = m; }
 // Run only the blocks for which filter(launch ordinal, linear block index) is true (for spot checks of large grids).
 void set_block_filter(bool (*filter)(int, unsigned)) { g_block_filter = filter; }
@@ -465,24 +499,18 @@ void launch_impl(dim3 grid, dim3 block, size_t lds_bytes, void (*fn)(void *), vo
 {
     g_fn = fn;
     g_arg = arg;
-    // LDS: exactly lds_bytes, flush against an inaccessible page, filled with NaN patterns before every workgroup
-    const size_t page = 4096, span = (lds_bytes + page - 1) / page * page;
-    unsigned char *m = static_cast<unsigned char *>(
-        mmap(nullptr, span + 2 * page, PROT_READ | PROT_WRITE, MAP_PRIVATE | MAP_ANONYMOUS, -1, 0));
-    if (m == MAP_FAILED)
-        die("mmap of LDS failed");
-    mprotect(m, page, PROT_NONE);
-    mprotect(m + page + span, page, PROT_NONE);
-    g_lds = m + page + span - ((lds_bytes + 15) / 16 * 16);
     const int launch = g_launch_index++;
-    for (unsigned b = 0; b < grid.x * grid.y * grid.z; ++b) {
-        if (g_block_filter && !g_block_filter(launch, b))
-            continue;
-        g_block = Idx{b % grid.x, (b / grid.x) % grid.y, b / (grid.x * grid.y)};
-        memset(g_lds, 0xFF, (lds_bytes + 15) / 16 * 16);
-        run_block(block);
+    std::vector<unsigned> ids;
+    for (unsigned b = 0; b < grid.x * grid.y * grid.z; ++b)
+        if (!g_block_filter || g_block_filter(launch, b))
+            ids.push_back(b);
+    if (ids.empty())
+        return;
+    if (g_cooperative) {
+        run_blocks(ids, grid, block, lds_bytes);  // all workgroups resident at once
+        return;
     }
-    munmap(m, span + 2 * page);
-    g_lds = nullptr;
+    for (unsigned b : ids)
+        run_blocks(std::vector<unsigned>{b}, grid, block, lds_bytes);
 }
 }  // namespace emu
