@@ -401,6 +401,20 @@ def test_emulated_64_channel_scan_matches_oracle_in_any_wave_order(emu_binary, t
     _check_case(emu_binary, tmp_path, "bf16", case, wide=True)
 
 
+@pytest.mark.parametrize("order", [0, 1, 9])
+def test_emulator_runs_workgroups_that_wait_for_each_other(tmp_path_factory, order):
+    """Self-test of the emulator's cooperative mode: a relay through all workgroups of a launch, in any wave order."""
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ with bf16 vector support found")
+    d = str(tmp_path_factory.mktemp("kernel_emu_coop"))
+    out = os.path.join(d, "coop_selftest")
+    r = subprocess.run([CLANG, "-std=c++17", "-O2", "-Wno-psabi", "-I", EMU, os.path.join(EMU, "coop_selftest.cpp"),
+                        os.path.join(EMU, "emu_rt.cpp"), "-o", out], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    r = subprocess.run([out, str(order)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "COOP OK" in r.stdout, r.stdout + r.stderr[-500:]
+
+
 def test_a_barrier_that_does_not_wait_is_noticed(emu_binary, tmp_path):
     """Self-test of the race check on the bf16 kernel.  The scan has one workgroup barrier, between the write of the
     starting state into LDS and the first hand-off; with it made not to wait, a wave reads the state before it is
