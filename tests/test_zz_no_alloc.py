@@ -49,3 +49,44 @@ def test_noalloc_rejects_oversized_plans():
         ssm.ssm_prefill_noalloc(plan.handle, 256, 256, 256, 256, 256, 256, None, 256, 256, None, 0, None)
     assert e.value.code == ssm.SSM_ERR_UNSUPPORTED_SHAPE
     plan.close()
+
+
+def test_noalloc_entry_under_graph_capture():
+    """What the entry point is for: a caller that records its work into a HIP graph and may not allocate while it
+    does.  The call is captured once (after one eager call, which sets the per-device tables' address up) and
+    replayed several times with eager work and synchronisations in between; every replay, on inputs refreshed in
+    place, equals the eager result."""
+    import paper_2411_19379_amd as ssm
+    shape = LayerShape(8, 64, 128, 2, 256, "bf16")
+    wl = make_workload(2, DEV, seed=303, batch=3, len_range=(100, 700), shape=shape)
+    init = list(wl.init_state)
+    s = wl.shape
+    plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
+    plan.workspace(torch.device(DEV))  # allocated before the capture
+    x = wl.inputs.x.clone()
+    y = torch.empty_like(x)
+    st = torch.empty((wl.n_ckpt, s.nheads, s.headdim, s.d_state), dtype=torch.float32, device=DEV)
+
+    def call(xin, y_out, st_out):
+        ssm.prefill(plan, xin, wl.inputs.dt, wl.A, wl.inputs.B, wl.inputs.C, wl.D, init, y_out=y_out, state_out=st_out,
+                    entry=ssm.ssm_prefill_noalloc)
+
+    call(x, y, st)  # eager: first use on this device
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(x, y, st)
+    g = torch.Generator(device=DEV).manual_seed(7)
+    for rep in range(4):
+        print(f"noalloc under graph capture: replay {rep}", flush=True)
+        x.copy_(torch.randn(x.shape, generator=g, device=DEV).to(x.dtype))  # new inputs, same buffers
+        y_ref, st_ref = torch.empty_like(y), torch.empty_like(st)
+        call(x, y_ref, st_ref)  # eager work between the replays
+        torch.cuda.synchronize()
+        y.fill_(float("nan"))
+        st.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16)), f"replay {rep}: y differs from the eager call"
+        assert torch.equal(st.view(torch.int32), st_ref.view(torch.int32)), f"replay {rep}: states differ"
+    plan.close()
