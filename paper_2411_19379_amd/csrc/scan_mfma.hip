@@ -18,16 +18,25 @@
 // blocks C_i.B_j and the tile's dt transposed to head-major.  The scan then loads every operand with fully
 // contiguous 1 KiB wave loads straight into registers: B and C never pass through its LDS.
 //
-// ssm_scan_mfma_kernel, one workgroup per (sequence, head, 32-channel slice).  The waves of a workgroup take the
-// sequence's tiles round-robin and each wave computes ALL of its tile: tables of decay factors, masked scores,
-// Gm.x, the tile-local state (16 MFMAs into 64 accumulator registers), S.C, y.  The running state S lives in LDS as
-// the register image of those accumulators; the wave whose turn it is reads it, adds its tile-local state
+// ssm_scan_mfma_kernel, one workgroup per (sequence, head, slice of 32 or 64 channels).  The waves of a workgroup
+// take the sequence's tiles round-robin and each wave computes ALL of its tile: tables of decay factors, the
+// tile-local state, S.C, the masked scores, Gm.x, y.  The running state S lives in LDS as the register image of the
+// accumulators of the tile-local state; the wave whose turn it is reads it, adds its tile-local state
 // (S <- e^{l_q} S + local), writes it back and uses the value it read for S.C.  The hand-off goes block by block of
 // 32 state indices; a counter per block in LDS says how many tiles have left their state there, and the wave of tile
 // k waits for the counter to reach k before it touches the block.  Nothing else orders the waves: there is no
-// workgroup barrier in the loop, each wave runs at its own pace, and 8 tiles are in flight per workgroup to hide
-// latencies.  A wave waits only for the wave of the tile before its own, which never waits for it, so the waits
-// cannot form a cycle; they are bounded all the same.
+// workgroup barrier in the loop, each wave runs at its own pace, and 8 or 12 tiles are in flight per workgroup to
+// hide latencies.  A wave waits only for the wave of the tile before its own, which never waits for it, so the
+// waits cannot form a cycle; they are bounded all the same.
+//
+// The blocks of 32 state indices are streamed through the registers: the B^T operand of a block, its part of the
+// tile-local state, its hand-off and its part of S.C, then the next block; the intra-tile term comes last and is
+// added onto e^{l_i} (S C_i) in the same accumulators.  x and y of a tile share one LDS tile per wave.
+//
+// With 64 channels per workgroup (two halves of 32) one set of operand loads (B^T, C, raw scores: 38 KiB per tile)
+// serves twice the rows: 54 KiB per 64 channels and tile instead of 2 x 47 KiB.  What limits the scan is the rate at
+// which a compute unit can pull operands through its L1, so this is the better variant whenever it still has enough
+// workgroups to fill the GPU (the plan decides); otherwise 32 channels per workgroup.
 //
 // Rounding: operands of the two long contractions (state update, S.C) are fp16 (11 bits: the decay-weighted x, the
 // copy of S, B and C), those of Gm.x are bf16 (x as stored, Gm rounded once); decay exponents, accumulators, the
@@ -61,8 +70,11 @@ constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_SCAN_WAVES
 #define SSM_SCAN_WAVES 8
 #endif
-constexpr int kWaves = SSM_SCAN_WAVES;   // waves per workgroup of the scan
-constexpr int kThreads = 64 * kWaves;
+#ifndef SSM_SCAN_WAVES_NARROW
+#define SSM_SCAN_WAVES_NARROW 12
+#endif
+constexpr int kWavesWide = SSM_SCAN_WAVES;           // waves per workgroup of the scan, 64 channels per workgroup
+constexpr int kWavesNarrow = SSM_SCAN_WAVES_NARROW;  // 32 channels per workgroup
 constexpr int kSpinLimit = 1 << 16;      // polls of a hand-off counter before a wave gives up waiting (milliseconds)
 constexpr int LDX = kPW;             // row stride of the x tile (unpadded on purpose: transpose reads)
 constexpr int LDY = kPW + 8;         // row stride of the y staging tile
@@ -347,24 +359,6 @@ __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
 }
 
 // ================================================================ the scan
-struct WaveLds {               // private to one wave
-    bf16_t Xr[kQ][LDX];        // x of the tile as loaded, token major
-    bf16_t Ys[kQ][LDY];        // y of the tile on its way to coalesced stores
-    float ell2[kQ];            // l_i * log2(e)
-    float cj[kQ];              // l_j * log2(e) - log2(dt_j)
-    float ei[kQ];              // e^{l_i}
-    float wt[kQ];              // e^{l_q - l_j} dt_j: weight of token j in the state update
-    float ri[kQ];              // e^{l_i - l_31}
-    float cf[kQ];              // e^{l_31 - l_j} dt_j
-};
-
-struct Lds {
-    float4 S[4][4][64];        // the running state: accumulator image [block of 32 n][element group a][lane]
-    int done[4];               // per block: how many tiles of the sequence have left their state in it
-    int pad[12];
-    WaveLds wv[kWaves];
-};
-
 // The 16 raw scores of a lane (accumulator image of a 32x32 block of Gm^T, fp16) as floats.
 __device__ __forceinline__ void unpack_scores(const uint4 &raw0, const uint4 &raw1, float (&v)[16])
 {
@@ -410,16 +404,38 @@ __device__ __forceinline__ void mask_diag(const uint4 &raw0, const uint4 &raw1, 
     pack_scores(v, g0, g1);
 }
 
-// ST: storage type of cached states (ssm_state_dtype_t).
-template <int ST>
-__global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
+template <int NC>
+struct WaveLdsT {                  // private to one wave
+    bf16_t XY[kQ][32 * NC + 8];    // x of the tile as loaded, token major; later y on its way to coalesced stores
+    float ell2[kQ];                // l_i * log2(e)
+    float cj[kQ];                  // l_j * log2(e) - log2(dt_j)
+    float ei[kQ];                  // e^{l_i}
+    float wt[kQ];                  // e^{l_q - l_j} dt_j: weight of token j in the state update
+    float ri[kQ];                  // e^{l_i - l_31}
+    float cf[kQ];                  // e^{l_31 - l_j} dt_j
+};
+
+template <int NC, int NW>
+struct LdsT {
+    float4 S[NC][4][4][64];        // the running state: [channel half][block of 32 n][element group a][lane]
+    int done[4];                   // per block of 32 n: how many tiles of the sequence have left their state in it
+    int pad[12];
+    WaveLdsT<NC> wv[NW];
+};
+
+// ST: storage type of cached states (ssm_state_dtype_t); NC: channel halves of 32 per workgroup; NW: waves.
+template <int ST, int NC, int NW>
+__global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
     void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
     const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
     int G, int p_split, int wg_per_xcd, int n_wg)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds &L = *reinterpret_cast<Lds *>(lds_raw);
+    constexpr int kCh = 32 * NC, LDXY = kCh + 8, kWaves = NW;
+    // rows of x / y: 4 NC lanes x 16 bytes per row, 64 / (4 NC) rows per wave instruction
+    constexpr int kLanesPerRow = 4 * NC, kRowsPerInstr = 64 / kLanesPerRow, kRowInstrs = kQ / kRowsPerInstr;
+    LdsT<NC, NW> &L = *reinterpret_cast<LdsT<NC, NW> *>(lds_raw);
 
     // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical ids (same head,
     // then same group) share an XCD's L2.
@@ -433,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     const int h = (wg / p_split) % H;
     const int seq = wg / (p_split * H);
     const int g = h / (H / G);
-    const int pbase = ps * kPW;
+    const int pbase = ps * kCh;
     const float Ah = A_[h], Dh = D_[h];
     const void *init = init_ptrs ? init_ptrs[seq] : nullptr;
     const SsmSeq sq = seqs[seq];
@@ -442,349 +458,13 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma_kernel(
     if (n_tiles <= 0)
         return;  // empty sequence: the whole workgroup leaves before any barrier
 
-    WaveLds &W = L.wv[w];
+    WaveLdsT<NC> &W = L.wv[w];
     const int i = lane & 31, q = lane >> 5;
     const int g4 = lane >> 4;
     const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
     const int tr_row_nat = 8 * (g4 >> 1) + ((lane & 15) >> 2);  // tokens 16 ks + 8 q + e (state update)
     const int tr_row_sc = 4 * (g4 >> 1) + ((lane & 15) >> 2);   // tokens 8 (e/4) + 4 q + e%4 (score order)
-    const int tok_l = lane >> 2, xcol = 8 * (lane & 3);
-    const size_t state_row = ((size_t)h * P + pbase + i) * kN + 4 * q;  // + 32 nb + 8 a: this lane's 4 state values
-    const uint32_t xrow_b = (uint32_t)H * P * 2;                         // bytes per token row of x and y
-    const unsigned char *xh = reinterpret_cast<const unsigned char *>(x) + ((size_t)h * P + pbase) * 2;  // uniform
-    unsigned char *yh = reinterpret_cast<unsigned char *>(y) + ((size_t)h * P + pbase) * 2;
-    const uint32_t xoff_lane = tok_l * xrow_b + xcol * 2;               // row tok_l, this lane's 16 bytes
-    const uint32_t lane16 = lane * 16;
-
-    // The state the sequence starts from (its cached state or zero) goes into LDS the way a tile would have left it.
-    for (int blk = w; blk < 16; blk += kWaves) {
-        const int nb = blk >> 2, a = blk & 3;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (init)
-            v = load_state4(init, state_row + 32 * nb + 8 * a, ST);
-        L.S[nb][a][lane] = v;
-    }
-    if (threadIdx.x < 4)
-        L.done[threadIdx.x] = 0;
-    lds_barrier();  // the only workgroup barrier: the starting state and the counters are in place
-    SSM_TRACE_DECL
-    constexpr uint32_t kBfOff = kCfWords * 16, kCbOff = (kCfWords + kBfWords) * 16;
-    const unsigned char *img_g = reinterpret_cast<const unsigned char *>(frags) + (size_t)g * kMfmaTileGroupBytes;
-
-    // What a tile needs first (dt, x, the raw scores and the B^T operand) is loaded one tile of this wave ahead:
-    // the loads of the next tile are issued before the epilogue of the current one and are in flight under it.
-    uint32_t dt_raw = 0;
-    uint4 xr[4], cb[3][2], bf[4][4];
-    auto issue_first_loads = [&](int tile_idx, const SsmTile &tl, bool live) {
-        const rsrc_t img =
-            make_rsrc(img_g + (size_t)tile_idx * G * kMfmaTileGroupBytes, live ? kMfmaTileGroupBytes : 0);
-        const rsrc_t dtr = make_rsrc(dt_t + ((size_t)tile_idx * H + h) * kQ, live ? kQ * 2 : 0);
-        dt_raw = __builtin_amdgcn_raw_buffer_load_b16(dtr, lane * 2, 0, 0);
-        // Rows past the end of a partial tile re-read the tile's last row: their weights are zero, so any finite
-        // value will do.
-        const rsrc_t xrs =
-            make_rsrc(xh + (size_t)tl.tok0 * xrow_b, live ? (uint32_t)(tl.len - 1) * xrow_b + kPW * 2 : 0);
-        if (tl.len == kQ) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                xr[kk] = buf_load16(xrs, xoff_lane, (uint32_t)(16 * kk) * xrow_b);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int tok = tok_l + 16 * kk < tl.len ? tok_l + 16 * kk : tl.len - 1;
-                xr[kk] = buf_load16(xrs, (uint32_t)tok * xrow_b + xcol * 2, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);  // dt and x first: the tile waits for them before anything else
-#pragma unroll
-        for (int blk = 0; blk < 3; ++blk)
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-                cb[blk][hf] = buf_load16(img, lane16, kCbOff + (blk * 2 + hf) * 1024);
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                bf[nb][ks] = buf_load16(img, lane16, kBfOff + (nb * 4 + ks) * 1024);
-    };
-    if (w >= n_tiles)
-        return;  // a wave without tiles; no barrier follows
-    int tile_idx = __builtin_amdgcn_readfirstlane(tile_begin + w);
-    SsmTile t = tiles[tile_idx], t_next = t;
-    issue_first_loads(tile_idx, t, true);
-    for (int k = w; k < n_tiles; k += kWaves) {  // this wave's tiles
-        __builtin_amdgcn_sched_barrier(0);
-        const rsrc_t img = make_rsrc(img_g + (size_t)tile_idx * G * kMfmaTileGroupBytes, kMfmaTileGroupBytes);
-        SSM_TRACE(8);
-        // C for the first half of the state indices: needed at the first hand-off
-        uint4 cfr[2][2][4];  // [half of the state indices][token half][k-step]
-#pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                cfr[0][ih][ks] = buf_load16(img, lane16, (ih * 8 + ks) * 1024);
-        SSM_TRACE(0);
-        phase_end();
-
-        // ---------------- phase 1: factor tables, x into LDS, decay-weighted x as the fp16 operand
-        float dl;
-        bool fast;
-        {
-            const float dtj = __uint_as_float(dt_raw << 16);
-            const float ell2 = wave_inclusive_sum(dtj * Ah) * kLog2e;
-            const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
-            dl = exp2_fast(last);   // padded tokens have dt = 0, so this is e^{l_len}
-            fast = last > -100.f;   // 2^+-100 is far inside the fp32 range: the two-factor form of the decay is safe
-            W.ell2[lane] = ell2;
-            W.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
-            W.ei[lane] = exp2_fast(ell2);
-            W.wt[lane] = exp2_fast(last - ell2) * dtj;
-            W.ri[lane] = exp2_fast(ell2 - e31);
-            W.cf[lane] = exp2_fast(e31 - ell2) * dtj;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                *reinterpret_cast<uint4 *>(&W.Xr[tok_l + 16 * kk][xcol]) = xr[kk];
-        }
-        lds_wait();
-        uint4 xw[4];
-        {
-            const bf16_t *px = &W.Xr[tr_row_nat][tr_col];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const uint4 xv = lds_frag_tr(px + 16 * ks * LDX, px + (16 * ks + 4) * LDX);
-                const float4 w0 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q]);
-                const float4 w1 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q + 4]);
-                xw[ks] = make_uint4(pack2_f16(w0.x * bf16_lo(xv.x), w0.y * bf16_hi(xv.x)),
-                                    pack2_f16(w0.z * bf16_lo(xv.y), w0.w * bf16_hi(xv.y)),
-                                    pack2_f16(w1.x * bf16_lo(xv.z), w1.y * bf16_hi(xv.z)),
-                                    pack2_f16(w1.z * bf16_lo(xv.w), w1.w * bf16_hi(xv.w)));
-            }
-        }
-        SSM_TRACE(1);
-        phase_end();
-
-        // ---------------- phase 2: tile-local state sum_j (e^{l_q-l_j} dt_j x_j) B_j^T on the matrix cores; under
-        // it, the loads of C for the second half of the state indices and the masked scores of the first token half
-        f32x16 Sl[4];
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-            Sl[nb] = zero16();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-                Sl[nb] = mfma_f16(bf[nb][ks], xw[ks], Sl[nb]);
-        __builtin_amdgcn_sched_barrier(0);  // the B^T operand's registers are free from here on
-#pragma unroll
-        for (int ih = 0; ih < 2; ++ih)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                cfr[1][ih][ks] = buf_load16(img, lane16, (ih * 8 + 4 + ks) * 1024);
-        uint4 gd[2][2], go[2];
-        if (fast)
-            mask_diag<true>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
-        else
-            mask_diag<false>(cb[0][0], cb[0][1], W, 0, i, q, Dh, gd[0][0], gd[0][1]);
-        SSM_TRACE(2);
-        phase_end();
-
-        // ---------------- phase 3: the other score blocks, x in score order, intra-tile term Gm.x (+ D x on the
-        // diagonal)
-        if (fast)
-            mask_diag<true>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
-        else
-            mask_diag<false>(cb[1][0], cb[1][1], W, 32, i, q, Dh, gd[1][0], gd[1][1]);
-        {
-            // off-diagonal block (keys 0..31, queries 32..63): unmasked, and both factors of
-            // e^{l_i-l_31} * e^{l_31-l_j} dt_j are <= 1 whatever the decay
-            float v[16];
-            unpack_scores(cb[2][0], cb[2][1], v);
-            const float ri = W.ri[32 + i];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const float4 f4 = *reinterpret_cast<const float4 *>(&W.cf[8 * a + 4 * q]);
-                v[4 * a + 0] *= ri * f4.x;
-                v[4 * a + 1] *= ri * f4.y;
-                v[4 * a + 2] *= ri * f4.z;
-                v[4 * a + 3] *= ri * f4.w;
-            }
-            pack_scores(v, go[0], go[1]);
-        }
-        f32x16 Yi[2];
-        {
-            uint4 xs[2][2];  // x^T of each token half, tokens in the order of the score blocks' rows
-#pragma unroll
-            for (int ih = 0; ih < 2; ++ih) {
-                const bf16_t *px = &W.Xr[32 * ih + tr_row_sc][tr_col];
-                xs[ih][0] = lds_frag_tr(px, px + 8 * LDX);
-                xs[ih][1] = lds_frag_tr(px + 16 * LDX, px + 24 * LDX);
-            }
-            Yi[0] = mfma_bf16(xs[0][0], gd[0][0], zero16());
-            Yi[1] = mfma_bf16(xs[1][0], gd[1][0], zero16());
-            Yi[0] = mfma_bf16(xs[0][1], gd[0][1], Yi[0]);
-            Yi[1] = mfma_bf16(xs[1][1], gd[1][1], Yi[1]);
-            Yi[1] = mfma_bf16(xs[0][0], go[0], Yi[1]);
-            Yi[1] = mfma_bf16(xs[0][1], go[1], Yi[1]);
-        }
-        SSM_TRACE(3);
-        phase_end();
-
-        // ---------------- the state hand-off, block by block of 32 state indices.  S as it was before this tile
-        // comes from LDS, where the wave of the previous tile left that block; this tile's S goes back in its place.
-        // The value read also feeds S.C.
-        f32x16 Yo[2];
-        Yo[0] = zero16();
-        Yo[1] = zero16();
-        auto hand_off = [&](int nb) {
-            wait_counter(&L.done[nb], k);
-            SSM_TRACE(15);
-            float4 sp[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                sp[a] = L.S[nb][a][lane];
-            float4 sn[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                sn[a] = make_float4(__builtin_fmaf(dl, sp[a].x, Sl[nb][4 * a + 0]), __builtin_fmaf(dl, sp[a].y, Sl[nb][4 * a + 1]),
-                                    __builtin_fmaf(dl, sp[a].z, Sl[nb][4 * a + 2]), __builtin_fmaf(dl, sp[a].w, Sl[nb][4 * a + 3]));
-                L.S[nb][a][lane] = sn[a];
-            }
-            publish_counter(&L.done[nb], k + 1, lane);
-            if (t.ckpt_slot >= 0) {
-                const size_t slot_row = (size_t)t.ckpt_slot * H * P * kN + state_row + 32 * nb;
-#pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    store_state4(state_out, slot_row + 8 * a, sn[a], ST);
-            }
-            // S_s C_i over the 32 state indices of this block: two k-steps of 16
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const uint4 s16 = make_uint4(pack2_f16(sp[2 * hf].x, sp[2 * hf].y), pack2_f16(sp[2 * hf].z, sp[2 * hf].w),
-                                             pack2_f16(sp[2 * hf + 1].x, sp[2 * hf + 1].y),
-                                             pack2_f16(sp[2 * hf + 1].z, sp[2 * hf + 1].w));
-                Yo[0] = mfma_f16(s16, cfr[nb >> 1][0][2 * (nb & 1) + hf], Yo[0]);
-                Yo[1] = mfma_f16(s16, cfr[nb >> 1][1][2 * (nb & 1) + hf], Yo[1]);
-            }
-        };
-        const bool more = k + kWaves < n_tiles;
-        if (more)  // the descriptor of this wave's next tile
-            t_next = tiles[tile_idx + kWaves];
-        SSM_TRACE(4);
-        hand_off(0);
-        hand_off(1);
-        SSM_TRACE(5);
-        phase_end();
-        hand_off(2);
-        hand_off(3);
-        phase_end();
-        // The loads of this wave's next tile.  After its last tile the wave issues them once more with descriptors of
-        // size zero (and the current tile's addresses): such loads return zeros without touching memory, and the
-        // loop needs no second copy of its tail.
-        issue_first_loads(more ? tile_idx + kWaves : tile_idx, t_next, more);
-        phase_end();
-        {   // y = e^{l_i} (S C_i) + intra-tile term on its way to LDS
-#pragma unroll
-            for (int ih = 0; ih < 2; ++ih) {
-                const float ei = W.ei[32 * ih + i];
-                // Y^T[p, i]: element r of this lane is channel 8(r/4) + 4q + r%4 of token 32 ih + i
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const float v0 = __builtin_fmaf(ei, Yo[ih][4 * a + 0], Yi[ih][4 * a + 0]);
-                    const float v1 = __builtin_fmaf(ei, Yo[ih][4 * a + 1], Yi[ih][4 * a + 1]);
-                    const float v2 = __builtin_fmaf(ei, Yo[ih][4 * a + 2], Yi[ih][4 * a + 2]);
-                    const float v3 = __builtin_fmaf(ei, Yo[ih][4 * a + 3], Yi[ih][4 * a + 3]);
-                    *reinterpret_cast<uint2 *>(&W.Ys[32 * ih + i][8 * a + 4 * q]) = make_uint2(pack2_bf16(v0, v1), pack2_bf16(v2, v3));
-                }
-            }
-        }
-        SSM_TRACE(6);
-        lds_wait();
-
-        // ---------------- y from LDS to device memory in coalesced rows
-        {
-            const rsrc_t yrs = make_rsrc(yh + (size_t)t.tok0 * xrow_b, (uint32_t)(t.len - 1) * xrow_b + kPW * 2);
-            if (t.len == kQ) {  // full tile: no predication
-#pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    buf_store16(yrs, xoff_lane, (uint32_t)(16 * m) * xrow_b,
-                                *reinterpret_cast<const uint4 *>(&W.Ys[tok_l + 16 * m][xcol]));
-            } else {
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const int tok = tok_l + 16 * m;
-                    if (tok < t.len)
-                        buf_store16(yrs, xoff_lane, (uint32_t)(16 * m) * xrow_b,
-                                    *reinterpret_cast<const uint4 *>(&W.Ys[tok][xcol]));
-                }
-            }
-        }
-        SSM_TRACE(7);
-        phase_end();
-        t = t_next;
-        tile_idx += kWaves;
-    }
-    SSM_TRACE_FLUSH
-}
-
-// ================================================================ the scan, 64 channels per workgroup
-// Same algebra and the same hand-off as ssm_scan_mfma_kernel, but a wave's tile covers 64 channels (two halves of 32)
-// of its head, so that one set of operand loads (B^T, C, raw scores: 38 KiB per tile) serves twice the rows.  What
-// limits the scan is the rate at which a CU can pull operands through its L1; this variant needs 54 KiB per 64
-// channels and tile instead of 2 x 47 KiB.  It has half as many workgroups, so it is the better choice only when
-// those still fill the GPU.  To fit the registers it streams the blocks of 32 state indices: the B^T operand, the
-// tile-local state, the hand-off and S.C of one block at a time, the intra-tile term last, added onto
-// e^{l_i} (S C_i) in the same accumulators.
-constexpr int kPW64 = 64;
-constexpr int LDX64 = kPW64 + 8;  // row stride of the x / y tile of a wave (elements): 144 bytes
-
-struct Wave64Lds {                 // private to one wave
-    bf16_t XY[kQ][LDX64];          // x of the tile as loaded, token major; later y on its way to coalesced stores
-    float ell2[kQ], cj[kQ], ei[kQ], wt[kQ], ri[kQ], cf[kQ];  // as in WaveLds
-};
-
-struct Lds64 {
-    float4 S[2][4][4][64];         // the running state: [channel half][block of 32 n][element group a][lane]
-    int done[4];                   // per block of 32 n: how many tiles of the sequence have left their state in it
-    int pad[12];
-    Wave64Lds wv[kWaves];
-};
-
-template <int ST>
-__global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
-    const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
-    void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
-    const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
-    int G, int p_split, int wg_per_xcd, int n_wg)
-{
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds64 &L = *reinterpret_cast<Lds64 *>(lds_raw);
-
-    const int wg = (blockIdx.x & 7) * wg_per_xcd + (blockIdx.x >> 3);  // same renumbering as the 32-channel kernel
-    if (wg >= n_wg)
-        return;
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-    const int ps = wg % p_split;
-    const int h = (wg / p_split) % H;
-    const int seq = wg / (p_split * H);
-    const int g = h / (H / G);
-    const int pbase = ps * kPW64;
-    const float Ah = A_[h], Dh = D_[h];
-    const void *init = init_ptrs ? init_ptrs[seq] : nullptr;
-    const SsmSeq sq = seqs[seq];
-    const int tile_begin = sq.tile_begin;
-    const int n_tiles = sq.tile_end - sq.tile_begin;
-    if (n_tiles <= 0)
-        return;  // empty sequence: the whole workgroup leaves before any barrier
-
-    Wave64Lds &W = L.wv[w];
-    const int i = lane & 31, q = lane >> 5;
-    const int g4 = lane >> 4;
-    const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-    const int tr_row_nat = 8 * (g4 >> 1) + ((lane & 15) >> 2);  // tokens 16 ks + 8 q + e (state update)
-    const int tr_row_sc = 4 * (g4 >> 1) + ((lane & 15) >> 2);   // tokens 8 (e/4) + 4 q + e%4 (score order)
-    const int tok_l = lane >> 3, xcol = 8 * (lane & 7);          // x / y rows: 8 lanes x 16 bytes per 128-byte row
+    const int tok_l = lane / kLanesPerRow, xcol = 8 * (lane % kLanesPerRow);
     // + 32 c kN (channel half) + 32 nb + 8 a: this lane's 4 state values
     const size_t state_row = ((size_t)h * P + pbase + i) * kN + 4 * q;
     const uint32_t xrow_b = (uint32_t)H * P * 2;                         // bytes per token row of x and y
@@ -794,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
     const uint32_t lane16 = lane * 16;
 
     // The state the sequence starts from (its cached state or zero) goes into LDS the way a tile would have left it.
-    for (int blk = w; blk < 32; blk += kWaves) {
+    for (int blk = w; blk < 16 * NC; blk += kWaves) {
         const int c = blk >> 4, nb = (blk >> 2) & 3, a = blk & 3;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (init)
@@ -812,20 +492,20 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
     // After its last tile the wave issues these loads once more through descriptors of size zero (on the current
     // tile's addresses): they return zeros without touching memory, and the loop needs no second copy of its tail.
     uint32_t dt_raw = 0;
-    uint4 xr[8];
+    uint4 xr[kRowInstrs];
     auto issue_first_loads = [&](int tile_idx, const SsmTile &tl, bool live) {
         const rsrc_t dtr = make_rsrc(dt_t + ((size_t)tile_idx * H + h) * kQ, live ? kQ * 2 : 0);
         dt_raw = __builtin_amdgcn_raw_buffer_load_b16(dtr, lane * 2, 0, 0);
         const rsrc_t xrs =
-            make_rsrc(xh + (size_t)tl.tok0 * xrow_b, live ? (uint32_t)(tl.len - 1) * xrow_b + kPW64 * 2 : 0);
+            make_rsrc(xh + (size_t)tl.tok0 * xrow_b, live ? (uint32_t)(tl.len - 1) * xrow_b + kCh * 2 : 0);
         if (tl.len == kQ) {
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                xr[kk] = buf_load16(xrs, xoff_lane, (uint32_t)(8 * kk) * xrow_b);
+            for (int kk = 0; kk < kRowInstrs; ++kk)
+                xr[kk] = buf_load16(xrs, xoff_lane, (uint32_t)(kRowsPerInstr * kk) * xrow_b);
         } else {
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int tok = tok_l + 8 * kk < tl.len ? tok_l + 8 * kk : tl.len - 1;
+            for (int kk = 0; kk < kRowInstrs; ++kk) {
+                const int tok = tok_l + kRowsPerInstr * kk < tl.len ? tok_l + kRowsPerInstr * kk : tl.len - 1;
                 xr[kk] = buf_load16(xrs, (uint32_t)tok * xrow_b + xcol * 2, 0);
             }
         }
@@ -872,17 +552,17 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
             W.ri[lane] = exp2_fast(ell2 - e31);
             W.cf[lane] = exp2_fast(e31 - ell2) * dtj;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                *reinterpret_cast<uint4 *>(&W.XY[tok_l + 8 * kk][xcol]) = xr[kk];
+            for (int kk = 0; kk < kRowInstrs; ++kk)
+                *reinterpret_cast<uint4 *>(&W.XY[tok_l + kRowsPerInstr * kk][xcol]) = xr[kk];
         }
         lds_wait();
-        uint4 xw[2][4];
+        uint4 xw[NC][4];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
+        for (int c = 0; c < NC; ++c) {
             const bf16_t *px = &W.XY[tr_row_nat][32 * c + tr_col];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                const uint4 xv = lds_frag_tr(px + 16 * ks * LDX64, px + (16 * ks + 4) * LDX64);
+                const uint4 xv = lds_frag_tr(px + 16 * ks * LDXY, px + (16 * ks + 4) * LDXY);
                 const float4 w0 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q]);
                 const float4 w1 = *reinterpret_cast<const float4 *>(&W.wt[16 * ks + 8 * q + 4]);
                 xw[c][ks] = make_uint4(pack2_f16(w0.x * bf16_lo(xv.x), w0.y * bf16_hi(xv.x)),
@@ -897,30 +577,31 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
         phase_end();
 
         // ---------------- per block of 32 state indices: tile-local state, hand-off, S.C
-        f32x16 Yo[2][2];  // [channel half][token half]
+        f32x16 Yo[NC][2];  // [channel half][token half]
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int ih = 0; ih < 2; ++ih)
                 Yo[c][ih] = zero16();
         auto block = [&](int nb) {
-            f32x16 Sl[2];
-            Sl[0] = zero16();
-            Sl[1] = zero16();
+            f32x16 Sl[NC];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                Sl[0] = mfma_f16(bfb[ks], xw[0][ks], Sl[0]);
-                Sl[1] = mfma_f16(bfb[ks], xw[1][ks], Sl[1]);
-            }
+            for (int c = 0; c < NC; ++c)
+                Sl[c] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+                    Sl[c] = mfma_f16(bfb[ks], xw[c][ks], Sl[c]);
             __builtin_amdgcn_sched_barrier(0);
             if (nb < 3)
                 load_b(nb + 1);  // into the registers the MFMAs above have just read
             // S as it was before this tile comes from LDS, where the wave of the previous tile left the block; this
             // tile's S goes back in its place.  The value read also feeds S.C.
             wait_counter(&L.done[nb], k);
-            uint4 s16[2][2];
+            uint4 s16[NC][2];
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < NC; ++c) {
                 float4 sp[4];
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
@@ -949,7 +630,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-                for (int c = 0; c < 2; ++c) {
+                for (int c = 0; c < NC; ++c) {
                     Yo[c][0] = mfma_f16(s16[c][hf], cfr[0][hf], Yo[c][0]);
                     Yo[c][1] = mfma_f16(s16[c][hf], cfr[1][hf], Yo[c][1]);
                 }
@@ -977,7 +658,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
         for (int ih = 0; ih < 2; ++ih) {
             const float ei = W.ei[32 * ih + i];
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     Yo[c][ih][r] *= ei;
@@ -1008,13 +689,13 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
                 pack_scores(v, go[0], go[1]);
             }
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < NC; ++c) {
                 uint4 xs[2][2];  // x^T of each token half, tokens in the order of the score blocks' rows
 #pragma unroll
                 for (int ih = 0; ih < 2; ++ih) {
                     const bf16_t *px = &W.XY[32 * ih + tr_row_sc][32 * c + tr_col];
-                    xs[ih][0] = lds_frag_tr(px, px + 8 * LDX64);
-                    xs[ih][1] = lds_frag_tr(px + 16 * LDX64, px + 24 * LDX64);
+                    xs[ih][0] = lds_frag_tr(px, px + 8 * LDXY);
+                    xs[ih][1] = lds_frag_tr(px + 16 * LDXY, px + 24 * LDXY);
                 }
                 Yo[c][0] = mfma_bf16(xs[0][0], gd[0][0], Yo[c][0]);
                 Yo[c][1] = mfma_bf16(xs[1][0], gd[1][0], Yo[c][1]);
@@ -1031,7 +712,7 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
         // y on its way to LDS, over the x tile (every read of it has been issued, and LDS runs a wave's accesses in
         // order).  Y^T[p, i]: element r of this lane is channel 32 c + 8(r/4) + 4q + r%4 of token 32 ih + i
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int ih = 0; ih < 2; ++ih)
 #pragma unroll
@@ -1043,18 +724,18 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
 
         // ---------------- y from LDS to device memory in whole 128-byte rows
         {
-            const rsrc_t yrs = make_rsrc(yh + (size_t)t.tok0 * xrow_b, (uint32_t)(t.len - 1) * xrow_b + kPW64 * 2);
+            const rsrc_t yrs = make_rsrc(yh + (size_t)t.tok0 * xrow_b, (uint32_t)(t.len - 1) * xrow_b + kCh * 2);
             if (t.len == kQ) {  // full tile: no predication
 #pragma unroll
-                for (int m = 0; m < 8; ++m)
-                    buf_store16(yrs, xoff_lane, (uint32_t)(8 * m) * xrow_b,
-                                *reinterpret_cast<const uint4 *>(&W.XY[tok_l + 8 * m][xcol]));
+                for (int m = 0; m < kRowInstrs; ++m)
+                    buf_store16(yrs, xoff_lane, (uint32_t)(kRowsPerInstr * m) * xrow_b,
+                                *reinterpret_cast<const uint4 *>(&W.XY[tok_l + kRowsPerInstr * m][xcol]));
             } else {
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const int tok = tok_l + 8 * m;
+                for (int m = 0; m < kRowInstrs; ++m) {
+                    const int tok = tok_l + kRowsPerInstr * m;
                     if (tok < t.len)
-                        buf_store16(yrs, xoff_lane, (uint32_t)(8 * m) * xrow_b,
+                        buf_store16(yrs, xoff_lane, (uint32_t)(kRowsPerInstr * m) * xrow_b,
                                     *reinterpret_cast<const uint4 *>(&W.XY[tok][xcol]));
                 }
             }
@@ -1065,16 +746,14 @@ __global__ __launch_bounds__(kThreads) void ssm_scan_mfma64_kernel(
     }
 }
 
-// WIDE: 64 channels per workgroup instead of 32.
-template <int ST, bool WIDE>
+// NC channel halves of 32 per workgroup, NW waves.
+template <int ST, int NC, int NW>
 hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
                           hipStream_t stream)
 {
     static std::once_flag attr_once[64];
     static hipError_t attr_err[64];
-    constexpr size_t lds = WIDE ? sizeof(Lds64) : sizeof(Lds);
-    const void *kernel = WIDE ? reinterpret_cast<const void *>(ssm_scan_mfma64_kernel<ST>)
-                              : reinterpret_cast<const void *>(ssm_scan_mfma_kernel<ST>);
+    constexpr size_t lds = sizeof(LdsT<NC, NW>);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
@@ -1082,33 +761,28 @@ hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
     std::call_once(attr_once[dev], [&]() {
-        attr_err[dev] = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_err[dev] = hipFuncSetAttribute(reinterpret_cast<const void *>(ssm_scan_mfma_kernel<ST, NC, NW>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err[dev] != hipSuccess)
         return attr_err[dev];
     const int n_wg = plan->n_workgroups;
     const int per_xcd = (n_wg + 7) / 8;
-    if (WIDE)
-        hipLaunchKernelGGL((ssm_scan_mfma64_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
-                           static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
-                           args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
-                           args.p_split, per_xcd, n_wg);
-    else
-        hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST>), dim3((unsigned)(per_xcd * 8)), dim3(kThreads), lds, stream,
-                           static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
-                           args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
-                           args.p_split, per_xcd, n_wg);
+    hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST, NC, NW>), dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds, stream,
+                       static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y), args.state_out,
+                       args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G, args.p_split, per_xcd,
+                       n_wg);
     return hipGetLastError();
 }
 
-template <bool WIDE>
+template <int NC, int NW>
 hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
                              hipStream_t stream)
 {
     switch (args.state_dtype) {
-    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16, WIDE>(plan, args, frags, dt_t, stream);
-    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16, WIDE>(plan, args, frags, dt_t, stream);
-    default: return launch_scan_st<SSM_ST_F32, WIDE>(plan, args, frags, dt_t, stream);
+    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16, NC, NW>(plan, args, frags, dt_t, stream);
+    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16, NC, NW>(plan, args, frags, dt_t, stream);
+    default: return launch_scan_st<SSM_ST_F32, NC, NW>(plan, args, frags, dt_t, stream);
     }
 }
 
@@ -1133,7 +807,7 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
         if (e != hipSuccess)
             return e;
     }
-    if (args.P / args.p_split == kPW64)
-        return launch_scan_width<true>(plan, args, frags, dt_t, stream);
-    return launch_scan_width<false>(plan, args, frags, dt_t, stream);
+    if (args.P / args.p_split == 64)
+        return launch_scan_width<2, kWavesWide>(plan, args, frags, dt_t, stream);
+    return launch_scan_width<1, kWavesNarrow>(plan, args, frags, dt_t, stream);
 }

@@ -96,8 +96,8 @@ def emu_binary(tmp_path_factory):
 
 @pytest.fixture(scope="session")
 def emu_binary_4waves(tmp_path_factory):
-    """The matrix-core scan with 4 waves per workgroup instead of the shipped 8."""
-    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4"])
+    """The matrix-core scan with 4 waves per workgroup instead of the shipped 12 (32 channels) or 8 (64 channels)."""
+    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4", "-DSSM_SCAN_WAVES_NARROW=4"])
 
 
 @pytest.fixture(scope="session")
