@@ -37,9 +37,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # --calibrate-copy.  Keyed by the hash of the kernel source the counters were
 # taken on: once that source changes the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "7899ee796ec7ee1daf2cc178be4afd6ef7c4fb9e": {
-        "cfg3_7b_32k_bf16": {"fetch_bytes": 367781 * 2 * 1024, "write_bytes": 528477 * 1024},
-        "cfg4_7b_128k_ckpt4096_bf16": {"fetch_bytes": 1647322 * 2 * 1024, "write_bytes": 2228645 * 1024},
+    "79fc3943c64296aedbf3ca5ffa953e6206e7f035": {
+        "cfg3_7b_32k_bf16": {"fetch_bytes": 753784799, "write_bytes": 541168046},
+        "cfg4_7b_128k_ckpt4096_bf16": {"fetch_bytes": 3364226415, "write_bytes": 2282125528},
     },
 }
 

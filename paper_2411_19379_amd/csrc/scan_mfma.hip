@@ -42,16 +42,8 @@
 // copy of S, B and C), those of Gm.x are bf16 (x as stored, Gm rounded once); decay exponents, accumulators, the
 // carried state and checkpoints are fp32.
 #include <mutex>
-#include <type_traits>
 
 #include "device_utils.h"
-
-// Optional cycle-trace hooks for profiling builds; they expand to nothing here.
-#ifndef SSM_TRACE
-#define SSM_TRACE(slot)
-#define SSM_TRACE_DECL
-#define SSM_TRACE_FLUSH
-#endif
 
 namespace {
 
@@ -66,7 +58,6 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int kQ = kMfmaTileTokens;  // 64 tokens per tile
 constexpr int kN = 128;              // d_state
-constexpr int kPW = 32;              // channels per workgroup
 #ifndef SSM_SCAN_WAVES
 #define SSM_SCAN_WAVES 8
 #endif
@@ -76,8 +67,6 @@ constexpr int kPW = 32;              // channels per workgroup
 constexpr int kWavesWide = SSM_SCAN_WAVES;           // waves per workgroup of the scan, 64 channels per workgroup
 constexpr int kWavesNarrow = SSM_SCAN_WAVES_NARROW;  // 32 channels per workgroup
 constexpr int kSpinLimit = 1 << 16;      // polls of a hand-off counter before a wave gives up waiting (milliseconds)
-constexpr int LDX = kPW;             // row stride of the x tile (unpadded on purpose: transpose reads)
-constexpr int LDY = kPW + 8;         // row stride of the y staging tile
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Operand images of one (tile, group) in the workspace, in uint4 units of 64 lanes each.

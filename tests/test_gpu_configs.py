@@ -89,3 +89,15 @@ def test_fp32_mode_at_the_2p7b_layer_shape():
     y, st, info = gpu_run(wl, wl.init_state)
     assert info.path == 0
     compare_all_heads(wl, y, st, init_np, tol=1e-4, block=8)
+
+
+def test_fp32_mode_of_cfg1_at_full_size():
+    """The 2.7B-shaped 2K-token configuration with fp32 inputs and outputs (fp32 vector-ALU kernel, all 80 heads,
+    cached 1024-token prefix): the 1e-4 tolerance of the fp32 mode at a full layer."""
+    from workloads import LayerShape
+    say("cfg1 in fp32 mode: H=80 P=64 N=128 G=1, T=2048 after a 1024-token cached prefix; all 80 heads")
+    wl = make_workload(1, DEV, shape=LayerShape(80, 64, 128, 1, 256, "f32"))
+    init, st_o = prefix_init(wl)
+    y, st, info = gpu_run(wl, [init])
+    assert info.path == 0
+    compare_all_heads(wl, y, st, [st_o], tol=1e-4, block=80)
