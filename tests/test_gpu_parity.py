@@ -240,3 +240,16 @@ def test_profile_mark_event_sits_between_the_two_kernels():
     assert prep > 0 and scan > 0 and abs(prep + scan - call) <= 0.05 * call + 0.01
     assert torch.equal(y, y_ref) and torch.equal(st, st_ref), "the mark must not change results"
     plan.close()
+
+
+def test_decay_rates_far_beyond_the_usual_range():
+    """A scaled by up to 1000: tiles whose total decay falls below 2^-100 take the exact per-entry exponential in the
+    score mask instead of the two-factor form, decay-weighted inputs underflow to zero where the true weights are
+    negligible, and cached states are forgotten within a few tokens.  Nothing may overflow or turn into NaN, and the
+    oracle still agrees within the tolerance on every head."""
+    say("decay rates x1 .. x1000: H=6 P=64 N=128 G=2, 3 requests with cached states and mid-tile checkpoints")
+    shape = LayerShape(6, 64, 128, 2, 256, "bf16")
+    wl = make_workload(2, DEV, seed=77, batch=3, len_range=(150, 500), shape=shape)
+    wl.A = wl.A * torch.tensor([1.0, 5.0, 20.0, 60.0, 200.0, 1000.0], device=DEV)
+    init_np = [None if s is None else s.cpu().numpy() for s in wl.init_state]
+    check_workload(wl, init_np, expect_path=1)

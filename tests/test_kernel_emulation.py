@@ -199,6 +199,9 @@ CASES = {
     "odd": ((6, 24, 40, 3, 64), 2, dict(batch=4, len_range=(1, 90))),
     # a zero-length sequence inside the batch
     "empty_seq": ((2, 64, 128, 1, 64), 2, dict(batch=3, len_range=(30, 100))),
+    # decay rates from the usual range up to 400 times it: tiles whose total decay is below 2^-100 take one exponential
+    # per score instead of the two-factor form, and weights underflow to zero where the true ones are negligible
+    "strong_decay": ((3, 64, 128, 1, 64), 2, dict(batch=2, len_range=(60, 200), a_scale=[1.0, 40.0, 400.0])),
 }
 
 
@@ -207,7 +210,11 @@ def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None, wide=Fal
     if io == "f32" and P * N > 8192:
         pytest.skip("the fp32 vector kernel holds at most 8192 state elements per head")
     shape = LayerShape(nheads=H, headdim=P, d_state=N, ngroups=G, chunk=chunk, io_dtype=io)
+    kw = dict(kw)
+    a_scale = kw.pop("a_scale", None)
     wl = make_workload(cfg, "cpu", seed=11, shape=shape, **kw)
+    if a_scale is not None:
+        wl.A = wl.A * torch.tensor(a_scale, dtype=wl.A.dtype)
     if case == "empty_seq":
         wl = _with_empty_sequence(wl)
     init = list(wl.init_state)
@@ -394,7 +401,7 @@ def test_emulated_4wave_scan_matches_oracle_in_any_wave_order(emu_binary_4waves,
     _check_case(emu_binary_4waves, tmp_path, "bf16", case)
 
 
-@pytest.mark.parametrize("case", ["ragged", "long", "tiny", "p128", "empty_seq"])
+@pytest.mark.parametrize("case", ["ragged", "long", "tiny", "p128", "empty_seq", "strong_decay"])
 def test_emulated_64_channel_scan_matches_oracle_in_any_wave_order(emu_binary, tmp_path, case):
     """The variant of the matrix-core scan whose workgroups own 64 channels (the plan picks it for grids that fill a
     GPU; the emulation driver forces it): same checks as for the 32-channel kernel."""
