@@ -253,3 +253,34 @@ def test_decay_rates_far_beyond_the_usual_range():
     wl.A = wl.A * torch.tensor([1.0, 5.0, 20.0, 60.0, 200.0, 1000.0], device=DEV)
     init_np = [None if s is None else s.cpu().numpy() for s in wl.init_state]
     check_workload(wl, init_np, expect_path=1)
+
+
+@pytest.mark.parametrize("entry_name", ["ssm_prefill", "ssm_prefill_noalloc"])
+def test_many_short_sequences(entry_name):
+    """600 requests of 0 to 5 tokens, a third of them resuming from a cached state: sequence, tile and state-pointer
+    tables longer than one upload, empty sequences among them, every tile partial."""
+    import paper_2411_19379_amd as ssm
+    say(f"600 sequences of 0..5 tokens through {entry_name}")
+    shape = LayerShape(2, 64, 128, 1, 256, "bf16")
+    rs = np.random.RandomState(5)
+    lens = [int(v) for v in rs.randint(0, 6, size=600)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    g = torch.Generator(device=DEV).manual_seed(99)
+    from workloads.gen import draw_layer_inputs, draw_layer_params
+    A, D = draw_layer_params(shape, g, DEV)
+    inp = draw_layer_inputs(shape, T, g, DEV)
+    init = [torch.randn((2, 64, 128), generator=g, device=DEV) if (i % 3 == 0 and lens[i]) else None for i in range(600)]
+    ckpt = [[L] if L else [] for L in lens]
+    plan = ssm.Plan(2, 64, 128, 1, 256, "bf16", cu, ckpt)
+    y, st = ssm.prefill(plan, inp.x, inp.dt, A, inp.B, inp.C, D, init, entry=getattr(ssm, entry_name))
+    torch.cuda.synchronize()
+    assert plan.info.batch == 600 and plan.info.n_tiles == sum(1 for L in lens if L)
+    plan.close()
+    from oracle import ssm_prefill_oracle
+    y_ref, st_ref = ssm_prefill_oracle(inp.x.float().cpu().numpy(), inp.dt.float().cpu().numpy(), A.cpu().numpy(),
+                                       inp.B.float().cpu().numpy(), inp.C.float().cpu().numpy(), D.cpu().numpy(), cu,
+                                       [None if s is None else s.cpu().numpy() for s in init], ckpt)
+    e_y = assert_close(y.float().cpu().numpy(), y_ref, TOL["bf16"], "y")
+    e_s = assert_close(st.cpu().numpy(), st_ref, TOL["bf16"], "states")
+    say(f"    err_y={e_y:.2e} err_state={e_s:.2e}")
