@@ -63,3 +63,6 @@ constexpr size_t kMfmaDtBytes = 128;
 // still has at least this many workgroups with work: one per compute unit of the GPU this library is written for.
 constexpr int kMfmaWideChannels = 64;
 constexpr int kMfmaWideMinWorkgroups = 256;
+
+// The kernel in front of the scan works per (tile, group); below this many pairs each pair gets four workgroups.
+constexpr int kMfmaPrepSplitBelow = 256;

@@ -260,17 +260,25 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 v)
 
 __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
     const bf16_t *__restrict__ Bg, const bf16_t *__restrict__ Cg, const bf16_t *__restrict__ dt,
-    const SsmTile *__restrict__ tiles, uint4 *__restrict__ frags, bf16_t *__restrict__ dt_t, int H, int G, int n_tiles)
+    const SsmTile *__restrict__ tiles, uint4 *__restrict__ frags, bf16_t *__restrict__ dt_t, int H, int G, int n_tiles,
+    int parts)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     PrepLds &L = *reinterpret_cast<PrepLds *>(lds_raw);
-    const int tile = blockIdx.x / G, g = blockIdx.x % G;
+    // parts = 1: one workgroup per (tile, group), its wave w writes quarter w of the operand images.  parts = 4 (small
+    // grids, which would leave most of the GPU idle): four workgroups per (tile, group), workgroup `part` writes
+    // quarter `part`, a sixteenth per wave, and transposes a quarter of the heads' dt.
+    const int tg = blockIdx.x / parts, part = blockIdx.x % parts;
+    const int tile = tg / G, g = tg % G;
     if (tile >= n_tiles)
         return;
     const SsmTile t = tiles[tile];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hg = H / G;  // heads of this group: g * hg .. g * hg + hg - 1
+    const int quarter = parts == 1 ? w : part;                 // which quarter of the images this wave works on
+    const int sub0 = parts == 1 ? 0 : w, sub1 = parts == 1 ? 4 : w + 1;  // and which sixteenths of it
+    const int h_lo = hg * part / parts, h_hi = hg * (part + 1) / parts;   // heads whose dt this workgroup transposes
 
     // B and C rows, 16 lanes per 256-byte row; rows past the end of a partial tile are zero
     {
@@ -290,9 +298,9 @@ __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
     }
     // dt of the tile, transposed to head-major rows of 64 tokens, kDtHeads heads at a time.  The barrier after the
     // first pass's loads also publishes the B and C tiles.
-    for (int h0 = 0; h0 < hg; h0 += kDtHeads) {
-        const int nh = hg - h0 < kDtHeads ? hg - h0 : kDtHeads;
-        if (h0 > 0)
+    for (int h0 = h_lo; h0 < h_hi || h0 == h_lo; h0 += kDtHeads) {  // at least one pass: its barrier is needed
+        const int nh = h_hi - h0 < kDtHeads ? (h_hi - h0 > 0 ? h_hi - h0 : 0) : kDtHeads;
+        if (h0 > h_lo)
             __syncthreads();  // the previous pass has been written out
         for (int idx = tid; idx < kQ * nh; idx += kPrepThreads) {
             const int tok = idx / nh, hh = idx % nh;
@@ -308,13 +316,12 @@ __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
         }
     }
 
-    uint4 *out = frags + (size_t)blockIdx.x * (kCfWords + kBfWords + kCbWords);
+    uint4 *out = frags + (size_t)tg * (kCfWords + kBfWords + kCbWords);
     const int i = lane & 31, q = lane >> 5;
     // C operand of S.C: lane (token i of a half, q), k-step ks: state indices 16 ks + 8 (e/4) + 4 q + e%4, the order
     // in which a lane holds a block of the state in its accumulators
-#pragma unroll
-    for (int f = 0; f < 4; ++f) {
-        const int idx = 4 * w + f, ih = idx >> 3, ks = idx & 7;
+    for (int f = sub0; f < sub1; ++f) {
+        const int idx = 4 * quarter + f, ih = idx >> 3, ks = idx & 7;
         const _Float16 *row = &L.Cs[32 * ih + i][16 * ks + 4 * q];
         const uint2 lo = *reinterpret_cast<const uint2 *>(row), hi = *reinterpret_cast<const uint2 *>(row + 8);
         out[(ih * 8 + ks) * 64 + lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
@@ -324,16 +331,15 @@ __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
         const int g4 = lane >> 4;
         const int tr_row = 8 * (g4 >> 1) + ((lane & 15) >> 2);
         const int tr_col = 16 * (g4 & 1) + 4 * (lane & 3);
-        const _Float16 *pb = &L.Bs[tr_row][32 * w + tr_col];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            out[kCfWords + (w * 4 + ks) * 64 + lane] = lds_frag_tr(pb + 16 * ks * LDPB, pb + (16 * ks + 4) * LDPB);
+        const _Float16 *pb = &L.Bs[tr_row][32 * quarter + tr_col];
+        for (int ks = sub0; ks < sub1; ++ks)
+            out[kCfWords + (quarter * 4 + ks) * 64 + lane] = lds_frag_tr(pb + 16 * ks * LDPB, pb + (16 * ks + 4) * LDPB);
     }
     // raw score blocks Gm^T[j, i] = B_j . C_i: block 0 keys and queries 0..31, block 1 keys and queries 32..63,
     // block 2 keys 0..31 and queries 32..63; kept as the 16 accumulator elements of every lane, in fp16
-    if (w < 3) {
-        const _Float16 *pb = &L.Bs[(w == 1 ? 32 : 0) + i][8 * q];
-        const _Float16 *pc = &L.Cs[(w == 0 ? 0 : 32) + i][8 * q];
+    if (quarter < 3 && (parts == 1 || w == 0)) {
+        const _Float16 *pb = &L.Bs[(quarter == 1 ? 32 : 0) + i][8 * q];
+        const _Float16 *pc = &L.Cs[(quarter == 0 ? 0 : 32) + i][8 * q];
         f32x16 acc = zero16();
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(kPrepThreads) void ssm_prep_kernel(
                            acc);
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
-            out[kCfWords + kBfWords + (w * 2 + hf) * 64 + lane] =
+            out[kCfWords + kBfWords + (quarter * 2 + hf) * 64 + lane] =
                 make_uint4(pack2_f16(acc[8 * hf + 0], acc[8 * hf + 1]), pack2_f16(acc[8 * hf + 2], acc[8 * hf + 3]),
                            pack2_f16(acc[8 * hf + 4], acc[8 * hf + 5]), pack2_f16(acc[8 * hf + 6], acc[8 * hf + 7]));
     }
@@ -785,9 +791,11 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
     uint4 *frags = static_cast<uint4 *>(workspace);
     bf16_t *dt_t = reinterpret_cast<bf16_t *>(static_cast<unsigned char *>(workspace) +
                                               (size_t)n_tiles * args.G * kMfmaTileGroupBytes);
-    hipLaunchKernelGGL(ssm_prep_kernel, dim3((unsigned)n_tiles * (unsigned)args.G), dim3(kPrepThreads), sizeof(PrepLds),
-                       stream, static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C),
-                       static_cast<const bf16_t *>(args.dt), args.tiles, frags, dt_t, args.H, args.G, n_tiles);
+    // few (tile, group) pairs: four workgroups each, so that the preparation does not run on a corner of the GPU
+    const int parts = (long long)n_tiles * args.G < kMfmaPrepSplitBelow ? 4 : 1;
+    hipLaunchKernelGGL(ssm_prep_kernel, dim3((unsigned)n_tiles * (unsigned)args.G * (unsigned)parts), dim3(kPrepThreads),
+                       sizeof(PrepLds), stream, static_cast<const bf16_t *>(args.B), static_cast<const bf16_t *>(args.C),
+                       static_cast<const bf16_t *>(args.dt), args.tiles, frags, dt_t, args.H, args.G, n_tiles, parts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;

@@ -11,12 +11,12 @@
 #include "emu_host.h"
 namespace emu { void set_order_mode(int m); void set_block_filter(bool (*)(int, unsigned)); long switches(); }
 
-static int gH, gP, gG, g_per_xcd, g_psplit;
+static int gH, gP, gG, g_per_xcd, g_psplit, g_prep_parts = 1;
 static std::vector<int> g_wgs;   // logical workgroup ids to run
 static bool filter(int launch, unsigned b)
 {
-    if (launch == 0) {  // the kernel in front of the scan: block = tile * G + g; keep the groups of the selected heads
-        const int g = b % gG;
+    if (launch == 0) {  // the kernel in front of the scan, one or four blocks per (tile, group): keep the groups of the selected heads
+        const int g = (b / g_prep_parts) % gG;  // block = ((tile * G) + g) * parts + part
         for (int wg : g_wgs) if (((wg / g_psplit) % gH) / (gH / gG) == g) return true;
         return false;
     }
@@ -37,6 +37,7 @@ int main(int argc, char **argv)
     int32_t cu[2] = {0, T}, cuck[2] = {0, (int32_t)ck.size()};
     ssm_plan_t *plan; if (ssm_plan_create(&sh, 1, cu, cuck, ck.data(), &plan)) { printf("plan: %s\n", ssm_last_error()); return 1; }
     g_psplit = plan->p_split; g_per_xcd = (plan->n_workgroups + 7) / 8;
+    g_prep_parts = (long long)plan->tiles.size() * G < kMfmaPrepSplitBelow ? 4 : 1;
     g_wgs = {0, 1, plan->n_workgroups - 1};
     const size_t nx = (size_t)T * H * P, nb = (size_t)T * G * N, ndt = (size_t)T * H, nst = (size_t)H * P * N;
     printf("T=%d tiles=%zu wgs=%d ckpts=%zu; x %.2f GB\n", T, plan->tiles.size(), plan->n_workgroups, ck.size(), nx * 2 / 1e9);

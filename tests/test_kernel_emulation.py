@@ -193,6 +193,8 @@ CASES = {
     "tiny": ((2, 64, 128, 1, 64), 2, dict(batch=2, len_range=(1, 3))),
     # one 32-channel slice per head, several groups with several heads each, 32-token tiles
     "p32_groups": ((4, 32, 128, 2, 32), 2, dict(batch=2, len_range=(20, 120))),
+    # seven heads per group: the four workgroups per (tile, group) of the kernel in front of the scan share them 1, 2, 2, 2
+    "heads7": ((7, 32, 128, 1, 64), 2, dict(batch=2, len_range=(40, 150))),
     # four slices per head, large chunk
     "p128": ((1, 128, 128, 1, 256), 4, dict(seqlen=200, ckpt_every=64)),
     # shapes outside the matrix-core path (any storage type takes the fp32 vector kernel)
