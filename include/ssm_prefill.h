@@ -115,6 +115,24 @@ int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info);
 int ssm_plan_tile(const ssm_plan_t *plan, int32_t i, int32_t *tok0, int32_t *len,
                   int32_t *seq, int32_t *ckpt_slot);
 
+/* Launch order of the matrix-core scan, for inspection: how the planner spreads the chunked prefill of Section 4.1
+ * over the GPU when the batch mixes long and short requests (the request mix of Section 5.1's traces).  Work items
+ * are (rank of a non-empty sequence by decreasing tile count, head, channel slice), numbered by rank, then head, then
+ * slice; the launch has n_blocks workgroups, dealt round-robin to the GPU's 8 dies, and ssm_plan_launch_item tells
+ * which item a workgroup takes.
+ *   by_length  [batch]  host, out, may be NULL; by_length[r] = index of the sequence of rank r (ties: lower index first)
+ *   slices              out, may be NULL; channel slices per head (items per sequence = nheads * slices)
+ *   n_items             out, may be NULL; non-empty sequences * nheads * slices
+ *   n_blocks            out, may be NULL; workgroups of the launch (a multiple of 8, >= n_items)
+ * SSM_ERR_INVALID_ARG if plan is NULL. */
+int ssm_plan_launch_order(const ssm_plan_t *plan, int32_t *by_length, int32_t *slices, int32_t *n_items,
+                          int64_t *n_blocks);
+
+/* The work item (see ssm_plan_launch_order) of workgroup `block`, 0 <= block < n_blocks, or -1 if that workgroup has
+ * none and leaves at once.  Every item belongs to exactly one workgroup.  SSM_ERR_INVALID_ARG if a pointer is NULL or
+ * block is out of range. */
+int ssm_plan_launch_item(const ssm_plan_t *plan, int64_t block, int32_t *item);
+
 /* Bytes of device workspace ssm_prefill needs for this plan (may be 0): the
  * per-(tile, group) operands that the heads of a group share in the chunked
  * scan of Section 4.1.  The caller allocates it, 256-byte aligned, owns it,
@@ -179,7 +197,7 @@ int ssm_prefill(const ssm_plan_t *plan,
  *
  * Limits: at most 16384 tiles (ssm_plan_info n_tiles) and 1024 sequences per
  * call, otherwise SSM_ERR_UNSUPPORTED_SHAPE and nothing is enqueued.  The
- * array (272 KiB per GPU the library runs on, held until the process ends) is
+ * array (280 KiB per GPU the library runs on, held until the process ends) is
  * shared by every call on that GPU: calls that overlap on one GPU, on
  * different streams, race.  Calls on one stream are ordered by the stream.
  * Every call rewrites all it reads of the array, so nothing carries over from

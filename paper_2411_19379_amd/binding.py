@@ -73,6 +73,10 @@ def load_library():
                                     ctypes.POINTER(vp)]
     lib.ssm_plan_info.restype = ctypes.c_int
     lib.ssm_plan_info.argtypes = [vp, ctypes.POINTER(SsmPlanInfo)]
+    lib.ssm_plan_launch_order.restype = ctypes.c_int
+    lib.ssm_plan_launch_order.argtypes = [vp, i32p, i32p, i32p, ctypes.POINTER(ctypes.c_int64)]
+    lib.ssm_plan_launch_item.restype = ctypes.c_int
+    lib.ssm_plan_launch_item.argtypes = [vp, ctypes.c_int64, i32p]
     lib.ssm_plan_tile.restype = ctypes.c_int
     lib.ssm_plan_tile.argtypes = [vp, ctypes.c_int32, i32p, i32p, i32p, i32p]
     lib.ssm_plan_workspace_bytes.restype = ctypes.c_int
@@ -137,6 +141,20 @@ def ssm_plan_tile(plan: int, i: int):
     v = [ctypes.c_int32() for _ in range(4)]
     _check(load_library().ssm_plan_tile(plan, i, *[ctypes.byref(c) for c in v]))
     return tuple(c.value for c in v)  # tok0, len, seq, ckpt_slot
+
+
+def ssm_plan_launch_order(plan: int, batch: int):
+    by_length = (ctypes.c_int32 * max(batch, 1))()
+    slices, n_items, n_blocks = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+    _check(load_library().ssm_plan_launch_order(plan, by_length, ctypes.byref(slices), ctypes.byref(n_items),
+                                                ctypes.byref(n_blocks)))
+    return list(by_length)[:batch], slices.value, n_items.value, n_blocks.value
+
+
+def ssm_plan_launch_item(plan: int, block: int) -> int:
+    item = ctypes.c_int32()
+    _check(load_library().ssm_plan_launch_item(plan, block, ctypes.byref(item)))
+    return item.value
 
 
 def ssm_plan_workspace_bytes(plan: int) -> int:
@@ -224,6 +242,9 @@ class Plan:
 
     def tiles(self):
         return [ssm_plan_tile(self.handle, i) for i in range(self.info.n_tiles)]
+
+    def launch_order(self):
+        return ssm_plan_launch_order(self.handle, self.info.batch)
 
     def workspace(self, device):
         """The plan's device workspace as a torch tensor (allocated once per device, reused by every call)."""

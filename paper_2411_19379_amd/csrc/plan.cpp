@@ -2,9 +2,11 @@
 // Nothing in this file touches the GPU.
 #include "plan.h"
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <numeric>
 
 static thread_local std::string g_last_error;
 
@@ -177,8 +179,25 @@ extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
         return fail(SSM_ERR_UNSUPPORTED_SHAPE, "batch*nheads too large for one launch");
     }
     plan->n_workgroups = (int32_t)wgs;
+    ssm_plan_order_sequences(plan);
     *out = plan;
     return SSM_OK;
+}
+
+void ssm_plan_order_sequences(ssm_plan *plan)
+{
+    const int32_t batch = plan->batch;
+    std::vector<int32_t> order(batch);
+    std::iota(order.begin(), order.end(), 0);
+    auto n_tiles = [&](int32_t i) { return plan->seqs[i].tile_end - plan->seqs[i].tile_begin; };
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return n_tiles(a) > n_tiles(b); });
+    int64_t n_active = 0;
+    for (int32_t r = 0; r < batch; ++r) {
+        plan->seqs[r].by_length = order[r];
+        plan->seqs[r].reserved = 0;
+        n_active += n_tiles(order[r]) > 0;
+    }
+    plan->n_items = (int32_t)(n_active * plan->shape.nheads * plan->p_split);
 }
 
 extern "C" int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info)
@@ -207,6 +226,33 @@ extern "C" int ssm_plan_tile(const ssm_plan_t *plan, int32_t i, int32_t *tok0, i
     if (len) *len = t.len;
     if (seq) *seq = t.seq;
     if (ckpt_slot) *ckpt_slot = t.ckpt_slot;
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_launch_order(const ssm_plan_t *plan, int32_t *by_length, int32_t *slices, int32_t *n_items,
+                                     int64_t *n_blocks)
+{
+    if (!plan)
+        return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
+    if (by_length)
+        for (int32_t r = 0; r < plan->batch; ++r)
+            by_length[r] = plan->seqs[r].by_length;
+    if (slices)
+        *slices = plan->p_split;
+    if (n_items)
+        *n_items = plan->n_items;
+    if (n_blocks)
+        *n_blocks = ssm_launch_blocks(plan->n_items);
+    return SSM_OK;
+}
+
+extern "C" int ssm_plan_launch_item(const ssm_plan_t *plan, int64_t block, int32_t *item)
+{
+    if (!plan || !item)
+        return fail(SSM_ERR_INVALID_ARG, "plan or item is NULL");
+    if (block < 0 || block >= ssm_launch_blocks(plan->n_items))
+        return fail(SSM_ERR_INVALID_ARG, "block outside the launch");
+    *item = ssm_launch_item((uint32_t)block, plan->n_items);
     return SSM_OK;
 }
 

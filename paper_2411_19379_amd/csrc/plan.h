@@ -18,11 +18,51 @@ struct SsmTile {
     int32_t seq;        // owning sequence
 };
 
-// Per sequence: its tiles are [tile_begin, tile_end) of the tile table.
+// Per sequence: its tiles are [tile_begin, tile_end) of the tile table.  The third field belongs to the table, not to
+// the sequence: entry r names the sequence of rank r when the sequences are ordered by decreasing number of tiles.
 struct SsmSeq {
     int32_t tile_begin;
     int32_t tile_end;
+    int32_t by_length;
+    int32_t reserved;
 };
+
+// Launch order of the matrix-core scan.  Its work items, one per (rank of a non-empty sequence, head, channel slice),
+// form a line ordered by rank, then head, then slice: longest sequences first.  The hardware deals the workgroups of a
+// launch round-robin to 8 dies (XCDs), each with its own L2 and 32 compute units that take one workgroup at a time.
+// The line is cut into runs of 32 items (of an eighth of the items, if there are fewer than 256), one run per die and
+// round; within a round the runs go to the dies in ascending order, in the next round in descending order, and so on,
+// so that every die works through a similar mix of long and short items, starts its longest first, and neighbouring
+// heads (which share operands) meet in one L2.
+constexpr int kXcds = 8;
+constexpr int kItemsPerRun = 32;
+
+#ifdef __HIPCC__
+#define SSM_HOST_DEVICE __host__ __device__
+#else
+#define SSM_HOST_DEVICE
+#endif
+// The item of workgroup `block` of the launch, or -1 if it has none.  The launch has ssm_launch_blocks(n_items) blocks.
+SSM_HOST_DEVICE inline uint32_t ssm_launch_run_length(int64_t n_items)
+{
+    if (n_items >= kXcds * kItemsPerRun)
+        return kItemsPerRun;
+    return n_items > 0 ? (uint32_t)((n_items + kXcds - 1) / kXcds) : 1u;
+}
+SSM_HOST_DEVICE inline int32_t ssm_launch_item(uint32_t block, int32_t n_items)
+{
+    const uint32_t len = ssm_launch_run_length(n_items);
+    const uint32_t xcd = block % kXcds, k = block / kXcds;  // k-th workgroup of this die
+    const uint32_t round = k / len;
+    const uint32_t run = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
+    const uint32_t item = run * len + k % len;
+    return item < (uint32_t)n_items ? (int32_t)item : -1;
+}
+inline int64_t ssm_launch_blocks(int64_t n_items)
+{
+    const int64_t per_round = (int64_t)kXcds * ssm_launch_run_length(n_items);
+    return (n_items + per_round - 1) / per_round * per_round;
+}
 
 struct ssm_plan {
     ssm_shape_t shape;
@@ -33,6 +73,7 @@ struct ssm_plan {
     int32_t path = SSM_PATH_VALU_F32;
     int32_t p_split = 1;          // workgroups per (sequence, head): headdim is cut in p_split parts
     int32_t n_workgroups = 0;
+    int32_t n_items = 0;          // work items of the matrix-core scan: non-empty sequences x heads x p_split
     std::vector<SsmTile> tiles;
     std::vector<SsmSeq> seqs;
     // Device copies of the two tables and a buffer for the per-call state
@@ -49,6 +90,9 @@ struct ssm_plan {
 };
 
 void ssm_set_error(const std::string &msg);
+
+// (Re)builds seqs[].by_length and n_items from the tiles, the shape and p_split.
+void ssm_plan_order_sequences(ssm_plan *plan);
 
 // Tile lengths the two kernel families work with.
 constexpr int kValuTileTokens = 16;

@@ -424,7 +424,7 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
     void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
     const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
-    int G, int p_split, int wg_per_xcd, int n_wg)
+    int G, int p_split, int n_items)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     constexpr int kCh = 32 * NC, LDXY = kCh + 8, kWaves = NW;
@@ -432,17 +432,17 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
     constexpr int kLanesPerRow = 4 * NC, kRowsPerInstr = 64 / kLanesPerRow, kRowInstrs = kQ / kRowsPerInstr;
     LdsT<NC, NW> &L = *reinterpret_cast<LdsT<NC, NW> *>(lds_raw);
 
-    // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical ids (same head,
-    // then same group) share an XCD's L2.
-    const int wg = (blockIdx.x & 7) * wg_per_xcd + (blockIdx.x >> 3);
-    if (wg >= n_wg)
+    // The item of this workgroup in the launch order (longest sequences first; same head, then same group, next to
+    // each other on one XCD, so that they share its L2).
+    const int wg = ssm_launch_item(blockIdx.x, n_items);
+    if (wg < 0)
         return;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     const int ps = wg % p_split;
     const int h = (wg / p_split) % H;
-    const int seq = wg / (p_split * H);
+    const int seq = seqs[wg / (p_split * H)].by_length;
     const int g = h / (H / G);
     const int pbase = ps * kCh;
     const float Ah = A_[h], Dh = D_[h];
@@ -761,12 +761,12 @@ hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint
     });
     if (attr_err[dev] != hipSuccess)
         return attr_err[dev];
-    const int n_wg = plan->n_workgroups;
-    const int per_xcd = (n_wg + 7) / 8;
-    hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST, NC, NW>), dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds, stream,
-                       static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y), args.state_out,
-                       args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G, args.p_split, per_xcd,
-                       n_wg);
+    if (plan->n_items == 0)
+        return hipSuccess;  // every sequence is empty
+    hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST, NC, NW>), dim3((unsigned)ssm_launch_blocks(plan->n_items)), dim3(64 * NW), lds,
+                       stream, static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
+                       args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
+                       args.p_split, plan->n_items);
     return hipGetLastError();
 }
 

@@ -11,7 +11,7 @@
 #include "emu_host.h"
 namespace emu { void set_order_mode(int m); void set_block_filter(bool (*)(int, unsigned)); long switches(); }
 
-static int gH, gP, gG, g_per_xcd, g_psplit, g_prep_parts = 1;
+static int gH, gP, gG, g_psplit, g_items, g_prep_parts = 1;
 static std::vector<int> g_wgs;   // logical workgroup ids to run
 static bool filter(int launch, unsigned b)
 {
@@ -20,7 +20,7 @@ static bool filter(int launch, unsigned b)
         for (int wg : g_wgs) if (((wg / g_psplit) % gH) / (gH / gG) == g) return true;
         return false;
     }
-    const int wg = (b & 7) * g_per_xcd + (b >> 3);
+    const int wg = ssm_launch_item(b, g_items);  // one sequence: item = (head, slice)
     for (int w : g_wgs) if (w == wg) return true;
     return false;
 }
@@ -36,7 +36,7 @@ int main(int argc, char **argv)
     std::vector<int32_t> ck; for (int p = every; p <= T; p += every) ck.push_back(p);
     int32_t cu[2] = {0, T}, cuck[2] = {0, (int32_t)ck.size()};
     ssm_plan_t *plan; if (ssm_plan_create(&sh, 1, cu, cuck, ck.data(), &plan)) { printf("plan: %s\n", ssm_last_error()); return 1; }
-    g_psplit = plan->p_split; g_per_xcd = (plan->n_workgroups + 7) / 8;
+    g_psplit = plan->p_split; g_items = plan->n_items;
     g_prep_parts = (long long)plan->tiles.size() * G < kMfmaPrepSplitBelow ? 4 : 1;
     g_wgs = {0, 1, plan->n_workgroups - 1};
     const size_t nx = (size_t)T * H * P, nb = (size_t)T * G * N, ndt = (size_t)T * H, nst = (size_t)H * P * N;

@@ -105,6 +105,7 @@ int main(int argc, char **argv)
         // the 64-channel variant of the matrix-core scan, which the plan itself picks only for grids that fill a GPU
         plan->p_split = P / kMfmaWideChannels;
         plan->n_workgroups = batch * H * plan->p_split;
+        ssm_plan_order_sequences(plan);
     }
     const size_t nt = plan->tiles.size();
     SsmTile *tiles = static_cast<SsmTile *>(guarded(sizeof(SsmTile) * (nt ? nt : 1), end_aligned));

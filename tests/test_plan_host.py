@@ -18,7 +18,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "ssm_prefill.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ssm_[a-z0-9_]+)\s*\(", header))
-    assert names == {"ssm_plan_create", "ssm_plan_info", "ssm_plan_tile", "ssm_plan_workspace_bytes",
+    assert names == {"ssm_plan_create", "ssm_plan_info", "ssm_plan_tile", "ssm_plan_launch_order", "ssm_plan_launch_item",
+                     "ssm_plan_workspace_bytes",
                      "ssm_prefill", "ssm_prefill_noalloc", "ssm_state_advance", "ssm_conv1d_prefill",
                      "ssm_profile_mark", "ssm_plan_destroy", "ssm_last_error"}
     for n in names:
@@ -137,3 +138,57 @@ def test_null_arguments_and_destroy():
         ssm.ssm_plan_tile(plan.handle, 0)
     plan.close()
     plan.close()  # idempotent
+
+
+def test_launch_order_covers_every_item_once_and_balances_the_dies():
+    """The matrix-core scan's work items (rank by length, head, slice): empty sequences get none, every item belongs
+    to exactly one workgroup of the launch, each die (workgroups b with the same b % 8) meets its items in order of
+    decreasing sequence length, and a greedy schedule of each die's queue on its 32 compute units ends close to the
+    ideal (total work / 256) whenever there are enough items to go round."""
+    import heapq
+
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        batch = int(rng.integers(1, 40))
+        lens = rng.integers(0, 9000, size=batch) * (rng.random(batch) > 0.15)
+        if trial == 0:
+            lens = np.asarray([32768])
+        if trial == 1:
+            lens = np.zeros(5, dtype=np.int64)
+        if trial == 2:  # the 16 requests of the packed configuration
+            lens = np.asarray([615, 7105, 5883, 1198, 4728, 3752, 1172, 5308, 3632, 3866, 5581, 2229, 1333, 4866, 552, 7494])
+        batch = len(lens)
+        H = 80 if trial == 2 else int(rng.choice([2, 16, 80, 128]))
+        P = 64 if trial == 2 else int(rng.choice([32, 64, 128]))
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        plan = ssm.Plan(H, P, 128, 1 if H == 80 else 2, 64, "bf16", cu.tolist(), None)
+        by_length, slices, n_items, n_blocks = plan.launch_order()
+        tiles = np.zeros(batch, dtype=np.int64)
+        for (_, _, seq, _) in plan.tiles():
+            tiles[seq] += 1
+        assert sorted(by_length) == list(range(batch))
+        ranked = tiles[by_length]
+        assert all(ranked[i] >= ranked[i + 1] for i in range(batch - 1))
+        assert all(by_length[i] < by_length[i + 1] for i in range(batch - 1) if ranked[i] == ranked[i + 1])
+        per_seq = H * slices
+        assert slices in (P // 32, P // 64) and plan.info.n_workgroups == batch * per_seq
+        assert n_items == int((tiles > 0).sum()) * per_seq
+        assert n_blocks % 8 == 0 and n_items <= n_blocks < n_items + 256
+        if n_items < 256:
+            assert n_blocks < n_items + 8
+        items = [ssm.ssm_plan_launch_item(plan.handle, b) for b in range(n_blocks)]
+        assert sorted(i for i in items if i >= 0) == list(range(n_items))
+        with pytest.raises(ssm.SsmError):
+            ssm.ssm_plan_launch_item(plan.handle, n_blocks)
+        weight = np.repeat(ranked, per_seq)
+        ends = []
+        for die in range(8):
+            queue = [weight[i] for i in items[die::8] if i >= 0]
+            assert all(a >= b for a, b in zip(queue, queue[1:]))
+            cus = [0] * 32
+            for wq in queue:
+                heapq.heappush(cus, heapq.heappop(cus) + int(wq))
+            ends.append(max(cus))
+        if n_items >= 1024:
+            assert max(ends) <= 1.12 * weight[:n_items].sum() / 256 + weight.max() * 0.25, (ends, lens)
+        plan.close()
