@@ -152,12 +152,18 @@ __device__ __forceinline__ void phase_end()
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// The hand-off counters are read and written as LDS words, with DS instructions.  Through a generic pointer a volatile
+// access becomes a FLAT instruction, and the wait for a FLAT load also waits for every load from device memory that the
+// wave has in flight: the prefetched operands would sit on the chain from one tile's hand-off to the next.
+typedef __attribute__((address_space(3))) int lds_int_t;
+
 // Wait until `*counter` (in LDS) has reached `want`.  Bounded: a wave that gives up goes on with what is there, so
 // that every wave of the grid ends whatever happens.
 __device__ __forceinline__ void wait_counter(const int *counter, int want)
 {
+    const volatile lds_int_t *c = (const volatile lds_int_t *)counter;
     int polls = 0;
-    while (__builtin_amdgcn_readfirstlane(*static_cast<const volatile int *>(counter)) < want) {
+    while (__builtin_amdgcn_readfirstlane(*c) < want) {
         if (++polls > kSpinLimit)
             break;
         __builtin_amdgcn_s_sleep(1);
@@ -170,7 +176,7 @@ __device__ __forceinline__ void publish_counter(int *counter, int value, int lan
 {
     asm volatile("" ::: "memory");
     if (lane == 0)
-        *static_cast<volatile int *>(counter) = value;
+        *(volatile lds_int_t *)counter = value;
 }
 
 #define SSM_DPP(old, v, ctrl, row_mask, bound)                                                        \
@@ -592,7 +598,13 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
             if (nb < 3)
                 load_b(nb + 1);  // into the registers the MFMAs above have just read
             // S as it was before this tile comes from LDS, where the wave of the previous tile left the block; this
-            // tile's S goes back in its place.  The value read also feeds S.C.
+            // tile's S goes back in its place.  The value read also feeds S.C.  The tile-local state is pinned in front
+            // of the wait: everything that does not depend on the previous tile is issued before the wave starts to
+            // poll, so that only the read, the multiply-add and the write of the block lie between one tile's hand-off
+            // and the next.
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                asm volatile("" : "+v"(Sl[c]));
             wait_counter(&L.done[nb], k);
             uint4 s16[NC][2];
 #pragma unroll

@@ -49,6 +49,7 @@ _SUBST = [
     (r'asm volatile\("s_waitcnt lgkmcnt\(0\)" ::: "memory"\);', "emu::wave_sync(__LINE__);"),
     (r"extern __shared__ __align__\(16\) unsigned char lds_raw\[\];", "unsigned char *lds_raw = emu::lds_base();"),
     (r'asm volatile\("" ::: "memory"\);', ";"),  # compiler-only fence: nothing to emulate
+    (r'asm volatile\("" : "\+v"\(Sl\[c\]\)\);', ";"),  # pins a value in front of what follows: nothing to emulate
 ]
 
 
