@@ -163,23 +163,27 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events on the stream the kernels are launched on (torch's current stream): start, between the two
-    # kernels of the matrix-core scan (recorded by the library), end
-    ev = [(new_event(), new_event(), new_event()) for _ in range(args.steps)]
+    # HIP events on the stream the kernels are launched on (torch's current stream): start, after the operand
+    # preparation and after the scan kernel of the matrix-core path (both recorded by the library), end
+    ev = [(new_event(), new_event(), new_event(), new_event()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for a, m, b in ev:
+    # kernels behind the scan exist only when long sequences were cut into stretches (the carried states'
+    # contribution); only then is the second event recorded (every event in the stream costs a few microseconds)
+    cut = mfma and plan.info.n_stretches > wl.batch
+    for a, m, m2, b in ev:
         a.record()
         if mfma:
-            ssm.ssm_profile_mark(m.cuda_event)
+            ssm.ssm_profile_mark(m.cuda_event, m2.cuda_event if cut else None)
         step()
         b.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ssm.ssm_profile_mark(None)
-    call_ms = np.array([a.elapsed_time(b) for a, _, b in ev])
-    scan_ms = np.array([m.elapsed_time(b) for _, m, b in ev]) if mfma else call_ms
-    prep_ms = np.array([a.elapsed_time(m) for a, m, _ in ev]) if mfma else np.zeros_like(call_ms)
+    ssm.ssm_profile_mark(None, None)
+    call_ms = np.array([a.elapsed_time(b) for a, _, _, b in ev])
+    scan_ms = np.array([m.elapsed_time(m2 if cut else b) for _, m, m2, b in ev]) if mfma else call_ms
+    prep_ms = np.array([a.elapsed_time(m) for a, m, _, _ in ev]) if mfma else np.zeros_like(call_ms)
+    tail_ms = np.array([m2.elapsed_time(b) for _, _, m2, b in ev]) if cut else np.zeros_like(call_ms)
     ms_per_step = wall * 1e3 / args.steps
     T = wl.total_tokens
 
@@ -217,7 +221,7 @@ def main() -> int:
                    "checkpoints": n_ckpt,
                    "initial_states": 0 if init is None else sum(1 for v in init if v is not None),
                    "kernel_path": "mfma_bf16" if mfma else "valu_f32",
-                   "workgroups": plan.info.n_workgroups, "plan_ms": plan_ms,
+                   "workgroups": plan.info.n_workgroups, "stretches": plan.info.n_stretches, "plan_ms": plan_ms,
                    "call_ms_mean": float(call_ms.mean()), "call_ms_median": float(np.median(call_ms)),
                    "call_ms_min": float(call_ms.min())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -226,6 +230,7 @@ def main() -> int:
                      "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(scan_ms)),
                      "kernel_ms_min": float(scan_ms.min()),
                      "prep_kernel": "ssm_prep_kernel" if mfma else None, "prep_kernel_ms": float(prep_ms.mean()),
+                     "carry_kernels_ms": float(tail_ms.mean()),
                      "algorithmic_bytes": abytes,
                      "whole_call_frac": abytes / (float(call_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "mfma_tflops_dense_tile": flops / (kern_ms * 1e-3) / 1e12,

@@ -79,6 +79,8 @@ typedef struct {
     int32_t tile_tokens;   /* upper bound of a tile's length */
     int32_t path;          /* SSM_PATH_* */
     int32_t n_workgroups;  /* grid size of the scan kernel */
+    int32_t n_stretches;   /* stretches the scan walks: one per sequence, more when long sequences are cut
+                              (ssm_plan_stretch) */
 } ssm_plan_info_t;
 
 /*
@@ -132,6 +134,16 @@ int ssm_plan_launch_order(const ssm_plan_t *plan, int32_t *by_length, int32_t *s
  * none and leaves at once.  Every item belongs to exactly one workgroup.  SSM_ERR_INVALID_ARG if a pointer is NULL or
  * block is out of range. */
 int ssm_plan_launch_item(const ssm_plan_t *plan, int64_t block, int32_t *item);
+
+/* Stretch i (0 <= i < n_stretches) of the plan: the tiles [tile_begin, tile_end) that one workgroup per (head,
+ * channel slice) scans in order.  Normally a stretch is a whole sequence.  When a batch has too few sequences to
+ * occupy the GPU, a long sequence is cut into several stretches that are scanned at the same time, the later ones
+ * from a zero state (starts_from_zero = 1); the state their predecessor ends with is then carried over, and what it
+ * adds to their outputs and checkpoints (the recurrence of Section 2.1's state update is linear in the state) is added
+ * by a second kernel of the same call.  Results are those of the plain scan up to rounding.  Any output pointer may
+ * be NULL; SSM_ERR_INVALID_ARG if the plan is NULL or i is out of range. */
+int ssm_plan_stretch(const ssm_plan_t *plan, int32_t i, int32_t *tile_begin, int32_t *tile_end,
+                     int32_t *starts_from_zero);
 
 /* Bytes of device workspace ssm_prefill needs for this plan (may be 0): the
  * per-(tile, group) operands that the heads of a group share in the chunked
@@ -264,14 +276,16 @@ int ssm_conv1d_prefill(const ssm_plan_t *plan, int32_t channels, int32_t kernel_
 
 /*
  * Measurement aid (no passage of the paper: it serves the per-kernel timing of
- * the benchmark).  ssm_prefill on a matrix-core plan launches two kernels,
- * the operand preparation and the scan.  With a non-NULL hip_event (a
- * hipEvent_t created by the caller with timing enabled), every later
- * ssm_prefill / ssm_prefill_noalloc call of the calling thread records that
- * event on its stream between the two kernels, so that the caller can time
- * the scan kernel alone; NULL switches this off again.  Nothing else changes.
+ * the benchmark).  ssm_prefill on a matrix-core plan launches the operand
+ * preparation, the scan and, when long sequences were cut into stretches
+ * (ssm_plan_stretch), the kernels that add the carried states' contribution.
+ * With non-NULL events (hipEvent_t created by the caller with timing enabled),
+ * every later ssm_prefill / ssm_prefill_noalloc call of the calling thread
+ * records the first event on its stream after the preparation kernel and the
+ * second after the scan kernel, so that the caller can time each kernel alone;
+ * NULL switches an event off again.  Nothing else changes.
  */
-void ssm_profile_mark(void *hip_event);
+void ssm_profile_mark(void *after_first_kernel, void *after_second_kernel);
 
 /* Release the plan and the device tables it made on first use (Section 4.1's
  * plan lives exactly as long as the batch it describes).  NULL is accepted. */

@@ -45,7 +45,7 @@ class SsmPlanInfo(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_ckpt", ctypes.c_int32),
                 ("total_tokens", ctypes.c_int64), ("n_tiles", ctypes.c_int32),
                 ("tile_tokens", ctypes.c_int32), ("path", ctypes.c_int32),
-                ("n_workgroups", ctypes.c_int32)]
+                ("n_workgroups", ctypes.c_int32), ("n_stretches", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -77,6 +77,8 @@ def load_library():
     lib.ssm_plan_launch_order.argtypes = [vp, i32p, i32p, i32p, ctypes.POINTER(ctypes.c_int64)]
     lib.ssm_plan_launch_item.restype = ctypes.c_int
     lib.ssm_plan_launch_item.argtypes = [vp, ctypes.c_int64, i32p]
+    lib.ssm_plan_stretch.restype = ctypes.c_int
+    lib.ssm_plan_stretch.argtypes = [vp, ctypes.c_int32, i32p, i32p, i32p]
     lib.ssm_plan_tile.restype = ctypes.c_int
     lib.ssm_plan_tile.argtypes = [vp, ctypes.c_int32, i32p, i32p, i32p, i32p]
     lib.ssm_plan_workspace_bytes.restype = ctypes.c_int
@@ -92,7 +94,7 @@ def load_library():
     lib.ssm_conv1d_prefill.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.POINTER(vp), vp, vp,
                                        ctypes.c_int32, vp]
     lib.ssm_profile_mark.restype = None
-    lib.ssm_profile_mark.argtypes = [vp]
+    lib.ssm_profile_mark.argtypes = [vp, vp]
     lib.ssm_plan_destroy.restype = None
     lib.ssm_plan_destroy.argtypes = [vp]
     lib.ssm_last_error.restype = ctypes.c_char_p
@@ -143,6 +145,12 @@ def ssm_plan_tile(plan: int, i: int):
     return tuple(c.value for c in v)  # tok0, len, seq, ckpt_slot
 
 
+def ssm_plan_stretch(plan: int, i: int):
+    v = [ctypes.c_int32() for _ in range(3)]
+    _check(load_library().ssm_plan_stretch(plan, i, *[ctypes.byref(c) for c in v]))
+    return v[0].value, v[1].value, bool(v[2].value)  # tile_begin, tile_end, starts_from_zero
+
+
 def ssm_plan_launch_order(plan: int, batch: int):
     by_length = (ctypes.c_int32 * max(batch, 1))()
     slices, n_items, n_blocks = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
@@ -163,10 +171,12 @@ def ssm_plan_workspace_bytes(plan: int) -> int:
     return n.value
 
 
-def ssm_profile_mark(hip_event: Optional[int]):
-    """Have later prefill calls of this thread record `hip_event` (a raw hipEvent_t, e.g.
-    torch.cuda.Event(...).cuda_event after a first record) between their two kernels; None switches it off."""
-    load_library().ssm_profile_mark(ctypes.c_void_p(hip_event) if hip_event else None)
+def ssm_profile_mark(after_first: Optional[int], after_second: Optional[int] = None):
+    """Have later prefill calls of this thread record the given raw hipEvent_t handles (e.g.
+    torch.cuda.Event(...).cuda_event after a first record) after their first and after their second kernel;
+    None switches an event off."""
+    load_library().ssm_profile_mark(ctypes.c_void_p(after_first) if after_first else None,
+                                    ctypes.c_void_p(after_second) if after_second else None)
 
 
 def ssm_plan_destroy(plan: Optional[int]):
@@ -244,7 +254,10 @@ class Plan:
         return [ssm_plan_tile(self.handle, i) for i in range(self.info.n_tiles)]
 
     def launch_order(self):
-        return ssm_plan_launch_order(self.handle, self.info.batch)
+        return ssm_plan_launch_order(self.handle, self.info.n_stretches)
+
+    def stretches(self):
+        return [ssm_plan_stretch(self.handle, i) for i in range(self.info.n_stretches)]
 
     def workspace(self, device):
         """The plan's device workspace as a torch tensor (allocated once per device, reused by every call)."""

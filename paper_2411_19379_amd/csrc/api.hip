@@ -63,7 +63,7 @@ static hipError_t upload_table(void *dst, const void *src_host, size_t bytes, hi
 
 static size_t round16(size_t n) { return (n + 15) / 16 * 16; }
 
-// Device copies of a plan's tables on the current GPU; made on first use (three device allocations, the uploads
+// Device copies of a plan's tables on the current GPU; made on first use (four device allocations, the uploads
 // enqueued on `stream` and waited for once, so that later calls on any stream find them complete).
 static int device_tables(const ssm_plan *plan, hipStream_t stream, ssm_plan::DeviceTables *out)
 {
@@ -80,11 +80,13 @@ static int device_tables(const ssm_plan *plan, hipStream_t stream, ssm_plan::Dev
     const size_t tile_bytes = round16(plan->tiles.size() * sizeof(SsmTile));
     const size_t seq_bytes = round16(plan->seqs.size() * sizeof(SsmSeq));
     const size_t ptr_bytes = round16((size_t)plan->batch * sizeof(void *));
+    const size_t scan_seq_bytes = round16(plan->scan_seqs.size() * sizeof(SsmScanSeq));
     ssm_plan::DeviceTables t;
     t.device = dev;
     auto release = [&]() {
         (void)hipFree(t.tiles);
         (void)hipFree(t.seqs);
+        (void)hipFree(t.scan_seqs);
         (void)hipFree(t.ptrs);
     };
     if ((e = hipMalloc(&t.tiles, tile_bytes ? tile_bytes : 16)) != hipSuccess)
@@ -97,9 +99,15 @@ static int device_tables(const ssm_plan *plan, hipStream_t stream, ssm_plan::Dev
         release();
         return hip_fail("hipMalloc(state pointers)", e);
     }
+    if ((e = hipMalloc(&t.scan_seqs, scan_seq_bytes ? scan_seq_bytes : 16)) != hipSuccess) {
+        release();
+        return hip_fail("hipMalloc(stretch table)", e);
+    }
     e = upload_table(t.tiles, plan->tiles.data(), plan->tiles.size() * sizeof(SsmTile), stream);
     if (e == hipSuccess)
         e = upload_table(t.seqs, plan->seqs.data(), plan->seqs.size() * sizeof(SsmSeq), stream);
+    if (e == hipSuccess)
+        e = upload_table(t.scan_seqs, plan->scan_seqs.data(), plan->scan_seqs.size() * sizeof(SsmScanSeq), stream);
     if (e == hipSuccess)
         e = hipStreamSynchronize(stream);
     if (e != hipSuccess) {
@@ -151,10 +159,12 @@ static int check_prefill(const ssm_plan *plan, const void *x, const void *dt, co
     return SSM_OK;
 }
 
-static void fill_args(const ssm_plan *plan, ScanArgs &args, const void *tiles, const void *seqs)
+static void fill_args(const ssm_plan *plan, ScanArgs &args, const void *tiles, const void *seqs,
+                      const void *scan_seqs = nullptr)
 {
     args.tiles = static_cast<const SsmTile *>(tiles);
     args.seqs = static_cast<const SsmSeq *>(seqs);
+    args.scan_seqs = static_cast<const SsmScanSeq *>(scan_seqs);
     args.H = plan->shape.nheads;
     args.P = plan->shape.headdim;
     args.N = plan->shape.d_state;
@@ -167,7 +177,8 @@ static void fill_args(const ssm_plan *plan, ScanArgs &args, const void *tiles, c
 // starts from a cached state.
 static int launch_scan(const ssm_plan *plan, const void *x, const void *dt, const float *A, const void *B,
                        const void *C, const float *D, void *y_out, void *state_out, void *workspace,
-                       const void *d_tiles, const void *d_seqs, const void *d_init_ptrs, hipStream_t stream)
+                       const void *d_tiles, const void *d_seqs, const void *d_scan_seqs, const void *d_init_ptrs,
+                       hipStream_t stream)
 {
     ScanArgs args;
     args.x = x;
@@ -179,7 +190,7 @@ static int launch_scan(const ssm_plan *plan, const void *x, const void *dt, cons
     args.y = y_out;
     args.state_out = state_out;
     args.init_ptrs = static_cast<const void *const *>(d_init_ptrs);
-    fill_args(plan, args, d_tiles, d_seqs);
+    fill_args(plan, args, d_tiles, d_seqs, d_scan_seqs);
     const hipError_t e = plan->path == SSM_PATH_MFMA_BF16 ? launch_scan_mfma(plan, args, workspace, stream)
                                                           : launch_scan_valu(plan, args, stream);
     if (e != hipSuccess)
@@ -214,20 +225,22 @@ extern "C" int ssm_prefill(const ssm_plan_t *plan,
         if (e != hipSuccess)
             return hip_fail("upload of the initial-state pointers", e);
     }
-    return launch_scan(plan, x, dt, A, B, C, D, y_out, state_out, workspace, t.tiles, t.seqs,
+    return launch_scan(plan, x, dt, A, B, C, D, y_out, state_out, workspace, t.tiles, t.seqs, t.scan_seqs,
                        any_init ? t.ptrs : nullptr, stream);
 }
 
 // ---------------------------------------------------------------- the scan for callers that cannot allocate
-// The plan's tile table, its sequence table and the per-call state pointers go into a fixed device array that is
-// part of the library image, in place of the buffers ssm_prefill allocates on a plan's first use.  Every call on a
-// GPU shares that GPU's array: calls that overlap on one GPU race.  All three tables are rewritten by every call, so
+// The plan's tile table, its sequence and stretch tables and the per-call state pointers go into a fixed device array
+// that is part of the library image, in place of the buffers ssm_prefill allocates on a plan's first use.  Every call
+// on a GPU shares that GPU's array: calls that overlap on one GPU race.  All tables are rewritten by every call, so
 // nothing of an earlier call is read.
 constexpr size_t kNoAllocMaxTiles = 16384;
 constexpr size_t kNoAllocMaxBatch = 1024;
+constexpr size_t kNoAllocMaxStretches = kNoAllocMaxBatch + 256;  // cutting adds fewer than 256 stretches to a batch
 constexpr size_t kScratchSeqsOff = kNoAllocMaxTiles * sizeof(SsmTile);
 constexpr size_t kScratchPtrsOff = kScratchSeqsOff + kNoAllocMaxBatch * sizeof(SsmSeq);
-constexpr size_t kScratchBytes = kScratchPtrsOff + kNoAllocMaxBatch * sizeof(void *);
+constexpr size_t kScratchScanSeqsOff = kScratchPtrsOff + kNoAllocMaxBatch * sizeof(void *);
+constexpr size_t kScratchBytes = kScratchScanSeqsOff + kNoAllocMaxStretches * sizeof(SsmScanSeq);
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kMaxDevices = 64;
@@ -268,7 +281,8 @@ extern "C" int ssm_prefill_noalloc(const ssm_plan_t *plan,
         return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
     if (plan->total_tokens == 0 || plan->batch == 0)
         return SSM_OK;
-    if (plan->tiles.size() > kNoAllocMaxTiles || (size_t)plan->batch > kNoAllocMaxBatch)
+    if (plan->tiles.size() > kNoAllocMaxTiles || (size_t)plan->batch > kNoAllocMaxBatch ||
+        plan->scan_seqs.size() > kNoAllocMaxStretches)
         return fail(SSM_ERR_UNSUPPORTED_SHAPE,
                     "ssm_prefill_noalloc handles at most 16384 tiles and 1024 sequences per call");
     bool any_init = false;
@@ -284,12 +298,15 @@ extern "C" int ssm_prefill_noalloc(const ssm_plan_t *plan,
     hipError_t e = upload_table(base, plan->tiles.data(), plan->tiles.size() * sizeof(SsmTile), stream);
     if (e == hipSuccess)
         e = upload_table(base + kScratchSeqsOff, plan->seqs.data(), plan->seqs.size() * sizeof(SsmSeq), stream);
+    if (e == hipSuccess)
+        e = upload_table(base + kScratchScanSeqsOff, plan->scan_seqs.data(), plan->scan_seqs.size() * sizeof(SsmScanSeq),
+                         stream);
     if (e == hipSuccess && any_init)
         e = upload_table(base + kScratchPtrsOff, init_state_ptrs, (size_t)plan->batch * sizeof(void *), stream);
     if (e != hipSuccess)
         return hip_fail("upload of the plan's tables into the fixed device array", e);
     return launch_scan(plan, x, dt, A, B, C, D, y_out, state_out, workspace, base, base + kScratchSeqsOff,
-                       any_init ? base + kScratchPtrsOff : nullptr, stream);
+                       base + kScratchScanSeqsOff, any_init ? base + kScratchPtrsOff : nullptr, stream);
 }
 
 // ---------------------------------------------------------------- roll-forward / decode step
@@ -386,11 +403,15 @@ extern "C" int ssm_conv1d_prefill(const ssm_plan_t *plan, int32_t channels, int3
     return SSM_OK;
 }
 
-static thread_local hipEvent_t g_profile_event = nullptr;
+static thread_local hipEvent_t g_profile_event[2] = {nullptr, nullptr};
 
-hipEvent_t ssm_profile_event() { return g_profile_event; }
+hipEvent_t ssm_profile_event(int which) { return g_profile_event[which & 1]; }
 
-extern "C" void ssm_profile_mark(void *hip_event) { g_profile_event = static_cast<hipEvent_t>(hip_event); }
+extern "C" void ssm_profile_mark(void *after_first_kernel, void *after_second_kernel)
+{
+    g_profile_event[0] = static_cast<hipEvent_t>(after_first_kernel);
+    g_profile_event[1] = static_cast<hipEvent_t>(after_second_kernel);
+}
 
 extern "C" void ssm_plan_destroy(ssm_plan_t *plan)
 {
@@ -399,6 +420,7 @@ extern "C" void ssm_plan_destroy(ssm_plan_t *plan)
     for (const ssm_plan::DeviceTables &t : plan->device_tables) {
         (void)hipFree(t.tiles);
         (void)hipFree(t.seqs);
+        (void)hipFree(t.scan_seqs);
         (void)hipFree(t.ptrs);
     }
     delete plan;

@@ -68,6 +68,7 @@ struct ScanArgs {
     const void *const *init_ptrs;   // [batch] pointers to [H,P,N] in the state type, or NULL
     const SsmTile *tiles;
     const SsmSeq *seqs;
+    const SsmScanSeq *scan_seqs;    // matrix-core scan only
     int32_t H, P, N, G;
     int32_t p_split;
     int32_t state_dtype;            // ssm_state_dtype_t
@@ -76,8 +77,9 @@ struct ScanArgs {
 // Launchers implemented next to their kernels.
 hipError_t launch_scan_valu(const ssm_plan *plan, const ScanArgs &args, hipStream_t stream);
 hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream);
-// event to record between the two kernels of the matrix-core scan on the calling thread (nullptr: none)
-hipEvent_t ssm_profile_event();
+// events to record after the first and after the second kernel of the matrix-core scan on the calling thread
+// (nullptr: none)
+hipEvent_t ssm_profile_event(int which);
 bool state_advance_supports(const ssm_shape_t &s);
 hipError_t launch_state_advance(const ssm_plan *plan, const ScanArgs &args, void *const *d_state_ptrs,
                                 hipStream_t stream);

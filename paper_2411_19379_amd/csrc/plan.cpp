@@ -162,42 +162,109 @@ extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
         }
         plan->seqs[i].tile_end = (int32_t)plan->tiles.size();
     }
-    if (plan->path == SSM_PATH_MFMA_BF16 && s.headdim % kMfmaWideChannels == 0) {
-        // The matrix-core scan has a variant whose workgroups own 64 channels of a head instead of 32: one set of
-        // operand loads serves twice the rows, at half the number of workgroups.  It pays as soon as those still
-        // fill the GPU.
-        int64_t streams = 0;
-        for (int32_t i = 0; i < batch; ++i)
-            streams += cu_seqlens_host[i + 1] > cu_seqlens_host[i];
-        streams *= (int64_t)s.nheads * (s.headdim / kMfmaWideChannels);
-        if (streams >= kMfmaWideMinWorkgroups)
-            plan->p_split = s.headdim / kMfmaWideChannels;
-    }
     const int64_t wgs = (int64_t)batch * s.nheads * plan->p_split;
-    if (wgs > 0x7fffffffLL) {
+    if (wgs > 0x7fffffffLL / 4) {
         delete plan;
         return fail(SSM_ERR_UNSUPPORTED_SHAPE, "batch*nheads too large for one launch");
     }
     plan->n_workgroups = (int32_t)wgs;
-    ssm_plan_order_sequences(plan);
+    if (plan->path == SSM_PATH_MFMA_BF16)
+        ssm_plan_build_stretches(plan, kMfmaWideMinWorkgroups, kMfmaMinStretchTiles);
     *out = plan;
     return SSM_OK;
 }
 
-void ssm_plan_order_sequences(ssm_plan *plan)
+static void ssm_plan_order_sequences(ssm_plan *plan);
+
+void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_tiles)
 {
+    const ssm_shape_t &s = plan->shape;
     const int32_t batch = plan->batch;
-    std::vector<int32_t> order(batch);
+    auto seq_tiles = [&](int32_t i) { return plan->seqs[i].tile_end - plan->seqs[i].tile_begin; };
+    // A batch with too few (sequence, head, 64-channel slice) streams to occupy the GPU has its long sequences cut
+    // into stretches.  The scan has a variant whose workgroups own 64 channels of a head instead of 32: one set of
+    // operand loads serves twice the rows, at half the number of workgroups; it runs if those still fill the GPU.
+    std::vector<int32_t> parts(batch, 1);
+    plan->p_split = s.headdim / 32;
+    if (s.headdim % kMfmaWideChannels == 0) {
+        const int64_t per_seq = (int64_t)s.nheads * (s.headdim / kMfmaWideChannels);
+        int64_t active = 0;
+        for (int32_t i = 0; i < batch; ++i)
+            active += seq_tiles(i) > 0;
+        int64_t stretches = active;
+        if (active > 0 && active * per_seq < want_streams && min_tiles > 0) {
+            const int64_t k_want = (want_streams + active * per_seq - 1) / (active * per_seq);
+            stretches = 0;
+            for (int32_t i = 0; i < batch; ++i)
+                if (seq_tiles(i) > 0) {
+                    parts[i] = (int32_t)std::max<int64_t>(1, std::min<int64_t>(k_want, seq_tiles(i) / min_tiles));
+                    stretches += parts[i];
+                }
+        }
+        if (stretches * per_seq >= want_streams)
+            plan->p_split = s.headdim / kMfmaWideChannels;
+    }
+    plan->scan_seqs.clear();
+    plan->n_carry = 0;
+    plan->max_later_tiles = 0;
+    plan->carry_chains = false;
+    for (int32_t i = 0; i < batch; ++i) {
+        const int64_t begin = plan->seqs[i].tile_begin, n = seq_tiles(i);
+        for (int32_t k = 0; k < parts[i]; ++k) {
+            SsmScanSeq q = {};
+            q.tile_begin = (int32_t)(begin + n * k / parts[i]);
+            q.tile_end = (int32_t)(begin + n * (k + 1) / parts[i]);
+            q.init_seq = k == 0 ? i : -1;
+            q.carry_in = q.carry_out = -1;
+            if (k > 0) {
+                q.carry_in = plan->n_carry++;
+                plan->scan_seqs.back().carry_out = q.carry_in;
+                plan->max_later_tiles = std::max(plan->max_later_tiles, q.tile_end - q.tile_begin);
+                plan->carry_chains = plan->carry_chains || k > 1;
+            }
+            plan->scan_seqs.push_back(q);
+        }
+    }
+    for (size_t j = 0; j < plan->scan_seqs.size(); ++j)
+        if (plan->scan_seqs[j].carry_in >= 0)
+            plan->scan_seqs[plan->scan_seqs[j].carry_in].of_slot = (int32_t)j;
+    plan->n_workgroups = (int32_t)((int64_t)plan->scan_seqs.size() * s.nheads * plan->p_split);
+    ssm_plan_order_sequences(plan);
+}
+
+// Launch order of the stretches: longest first (ties: lower index first); stretches without tiles get no work item.
+static void ssm_plan_order_sequences(ssm_plan *plan)
+{
+    const int32_t n = (int32_t)plan->scan_seqs.size();
+    std::vector<int32_t> order(n);
     std::iota(order.begin(), order.end(), 0);
-    auto n_tiles = [&](int32_t i) { return plan->seqs[i].tile_end - plan->seqs[i].tile_begin; };
+    auto n_tiles = [&](int32_t i) { return plan->scan_seqs[i].tile_end - plan->scan_seqs[i].tile_begin; };
     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return n_tiles(a) > n_tiles(b); });
     int64_t n_active = 0;
-    for (int32_t r = 0; r < batch; ++r) {
-        plan->seqs[r].by_length = order[r];
-        plan->seqs[r].reserved = 0;
+    for (int32_t r = 0; r < n; ++r) {
+        plan->scan_seqs[r].by_length = order[r];
         n_active += n_tiles(order[r]) > 0;
     }
     plan->n_items = (int32_t)(n_active * plan->shape.nheads * plan->p_split);
+}
+
+SsmMfmaWorkspace ssm_mfma_workspace(const ssm_plan *plan)
+{
+    auto round256 = [](size_t n) { return (n + 255) / 256 * 256; };
+    SsmMfmaWorkspace w;
+    if (plan->path != SSM_PATH_MFMA_BF16)
+        return w;
+    const size_t n_tiles = plan->tiles.size(), H = (size_t)plan->shape.nheads;
+    w.images = 0;
+    w.dt_rows = w.images + n_tiles * (size_t)plan->shape.ngroups * kMfmaTileGroupBytes;
+    w.tile_decay = round256(w.dt_rows + n_tiles * H * kMfmaDtBytes);
+    w.carry = w.tile_decay;
+    w.total = w.tile_decay;
+    if (plan->n_carry > 0) {
+        w.carry = round256(w.tile_decay + n_tiles * H * sizeof(float));
+        w.total = round256(w.carry + (size_t)plan->n_carry * H * plan->shape.headdim * plan->shape.d_state * sizeof(float));
+    }
+    return w;
 }
 
 extern "C" int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info)
@@ -211,6 +278,7 @@ extern "C" int ssm_plan_info(const ssm_plan_t *plan, ssm_plan_info_t *info)
     info->tile_tokens = plan->tile_tokens;
     info->path = plan->path;
     info->n_workgroups = plan->n_workgroups;
+    info->n_stretches = plan->path == SSM_PATH_MFMA_BF16 ? (int32_t)plan->scan_seqs.size() : plan->batch;
     return SSM_OK;
 }
 
@@ -235,8 +303,8 @@ extern "C" int ssm_plan_launch_order(const ssm_plan_t *plan, int32_t *by_length,
     if (!plan)
         return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
     if (by_length)
-        for (int32_t r = 0; r < plan->batch; ++r)
-            by_length[r] = plan->seqs[r].by_length;
+        for (size_t r = 0; r < plan->scan_seqs.size(); ++r)
+            by_length[r] = plan->scan_seqs[r].by_length;
     if (slices)
         *slices = plan->p_split;
     if (n_items)
@@ -256,16 +324,35 @@ extern "C" int ssm_plan_launch_item(const ssm_plan_t *plan, int64_t block, int32
     return SSM_OK;
 }
 
+extern "C" int ssm_plan_stretch(const ssm_plan_t *plan, int32_t i, int32_t *tile_begin, int32_t *tile_end,
+                                int32_t *starts_from_zero)
+{
+    if (!plan)
+        return fail(SSM_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->path != SSM_PATH_MFMA_BF16) {
+        if (i < 0 || i >= plan->batch)
+            return fail(SSM_ERR_INVALID_ARG, "stretch index out of range");
+        if (tile_begin) *tile_begin = plan->seqs[i].tile_begin;
+        if (tile_end) *tile_end = plan->seqs[i].tile_end;
+        if (starts_from_zero) *starts_from_zero = 0;
+        return SSM_OK;
+    }
+    if (i < 0 || (size_t)i >= plan->scan_seqs.size())
+        return fail(SSM_ERR_INVALID_ARG, "stretch index out of range");
+    const SsmScanSeq &q = plan->scan_seqs[i];
+    if (tile_begin) *tile_begin = q.tile_begin;
+    if (tile_end) *tile_end = q.tile_end;
+    if (starts_from_zero) *starts_from_zero = q.carry_in >= 0;
+    return SSM_OK;
+}
+
 extern "C" int ssm_plan_workspace_bytes(const ssm_plan_t *plan, size_t *bytes)
 {
     if (!plan || !bytes)
         return fail(SSM_ERR_INVALID_ARG, "plan or bytes is NULL");
     // The running state never leaves the chip between tiles; the matrix-core scan needs room for the operands
-    // that the heads of a group share (written by its first kernel, read by its second).
-    size_t n = 0;
-    if (plan->path == SSM_PATH_MFMA_BF16)
-        n = plan->tiles.size() * ((size_t)plan->shape.ngroups * kMfmaTileGroupBytes +
-                                  (size_t)plan->shape.nheads * kMfmaDtBytes);
-    *bytes = (n + 255) / 256 * 256;
+    // that the heads of a group share (written by its first kernel, read by its second) and, when it cuts long
+    // sequences into stretches, for the states carried from one stretch to the next and each tile's total decay.
+    *bytes = ssm_mfma_workspace(plan).total;
     return SSM_OK;
 }

@@ -18,12 +18,26 @@ struct SsmTile {
     int32_t seq;        // owning sequence
 };
 
-// Per sequence: its tiles are [tile_begin, tile_end) of the tile table.  The third field belongs to the table, not to
-// the sequence: entry r names the sequence of rank r when the sequences are ordered by decreasing number of tiles.
+// Per sequence: its tiles are [tile_begin, tile_end) of the tile table.
 struct SsmSeq {
     int32_t tile_begin;
     int32_t tile_end;
-    int32_t by_length;
+};
+
+// What one workgroup of the matrix-core scan walks: a stretch of consecutive tiles of one sequence, either the whole
+// sequence or, when a batch has too few sequences to fill the GPU, one of several stretches a long sequence is cut
+// into.  A later stretch is scanned from a zero state at the same time as the ones before it; the state its
+// predecessor ends with reaches a carry slot, and a second kernel adds what that state contributes to the stretch's
+// outputs and checkpoints (the recurrence is linear in the state: the contribution to token t is the carried state
+// decayed from the stretch's start to t, times C_t).  The last two fields belong to the table, not to the stretch.
+struct SsmScanSeq {
+    int32_t tile_begin;
+    int32_t tile_end;
+    int32_t init_seq;   // sequence of the batch whose initial state the stretch starts from; -1: it starts from zero
+    int32_t carry_in;   // carry slot with the state the stretch truly starts from (a later stretch); -1: none
+    int32_t carry_out;  // carry slot that receives the state after the stretch's last tile; -1: none
+    int32_t by_length;  // entry r: the stretch of rank r when stretches are ordered by decreasing number of tiles
+    int32_t of_slot;    // entry c: the stretch whose carry_in is c
     int32_t reserved;
 };
 
@@ -73,9 +87,13 @@ struct ssm_plan {
     int32_t path = SSM_PATH_VALU_F32;
     int32_t p_split = 1;          // workgroups per (sequence, head): headdim is cut in p_split parts
     int32_t n_workgroups = 0;
-    int32_t n_items = 0;          // work items of the matrix-core scan: non-empty sequences x heads x p_split
+    int32_t n_items = 0;          // work items of the matrix-core scan: non-empty stretches x heads x p_split
+    int32_t n_carry = 0;          // carry slots: stretches that continue a sequence
+    int32_t max_later_tiles = 0;  // most tiles in any such stretch
+    bool carry_chains = false;    // some sequence is cut into three or more stretches
     std::vector<SsmTile> tiles;
     std::vector<SsmSeq> seqs;
+    std::vector<SsmScanSeq> scan_seqs;  // matrix-core scan only
     // Device copies of the two tables and a buffer for the per-call state
     // pointers, one set per GPU the plan has been used on.  A cache behind a
     // logically constant plan: filled on first use under `mu`.
@@ -83,6 +101,7 @@ struct ssm_plan {
         int device = -1;
         void *tiles = nullptr;  // SsmTile[n_tiles]
         void *seqs = nullptr;   // SsmSeq[batch]
+        void *scan_seqs = nullptr;  // SsmScanSeq[stretches]
         void *ptrs = nullptr;   // void*[batch], rewritten by every call that passes states
     };
     mutable std::mutex mu;
@@ -91,8 +110,20 @@ struct ssm_plan {
 
 void ssm_set_error(const std::string &msg);
 
-// (Re)builds seqs[].by_length and n_items from the tiles, the shape and p_split.
-void ssm_plan_order_sequences(ssm_plan *plan);
+// Matrix-core scan: (re)builds the stretches, p_split, the carry slots, the launch order and n_workgroups from the
+// tiles and the shape.  When the batch has fewer than `want_streams` (sequence, head, 64-channel slice) streams, long
+// sequences are cut into stretches of at least `min_tiles` tiles, as many as it takes to reach that number.
+void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_tiles);
+
+// Where the parts of the matrix-core scan's workspace start (bytes from its base), and its size.
+struct SsmMfmaWorkspace {
+    size_t images = 0;      // per (tile, group): kMfmaTileGroupBytes
+    size_t dt_rows = 0;     // per (tile, head): kMfmaDtBytes
+    size_t tile_decay = 0;  // per (head, tile): the tile's total log2 decay, fp32 (only with carry slots)
+    size_t carry = 0;       // per carry slot: [H, P, N] fp32
+    size_t total = 0;
+};
+SsmMfmaWorkspace ssm_mfma_workspace(const ssm_plan *plan);
 
 // Tile lengths the two kernel families work with.
 constexpr int kValuTileTokens = 16;
@@ -107,6 +138,10 @@ constexpr size_t kMfmaDtBytes = 128;
 // still has at least this many workgroups with work: one per compute unit of the GPU this library is written for.
 constexpr int kMfmaWideChannels = 64;
 constexpr int kMfmaWideMinWorkgroups = 256;
+
+// A sequence is cut into stretches only if each gets at least this many tiles (the second kernel's work per stretch
+// does not shrink with the stretch).
+constexpr int kMfmaMinStretchTiles = 64;
 
 // The kernel in front of the scan works per (tile, group); below this many pairs each pair gets four workgroups.
 constexpr int kMfmaPrepSplitBelow = 256;

@@ -429,8 +429,9 @@ template <int ST, int NC, int NW>
 __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ A_, const float *__restrict__ D_, bf16_t *__restrict__ y,
     void *__restrict__ state_out, const void *const *__restrict__ init_ptrs, const uint4 *__restrict__ frags,
-    const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmSeq *__restrict__ seqs, int H, int P,
-    int G, int p_split, int n_items)
+    const bf16_t *__restrict__ dt_t, const SsmTile *__restrict__ tiles, const SsmScanSeq *__restrict__ scan_seqs,
+    float *__restrict__ tile_decay, float *__restrict__ carry, int H, int P, int G, int p_split, int n_items,
+    int n_tiles_all)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     constexpr int kCh = 32 * NC, LDXY = kCh + 8, kWaves = NW;
@@ -448,16 +449,23 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
 
     const int ps = wg % p_split;
     const int h = (wg / p_split) % H;
-    const int seq = seqs[wg / (p_split * H)].by_length;
+    const int stretch = scan_seqs[wg / (p_split * H)].by_length;
     const int g = h / (H / G);
     const int pbase = ps * kCh;
     const float Ah = A_[h], Dh = D_[h];
-    const void *init = init_ptrs ? init_ptrs[seq] : nullptr;
-    const SsmSeq sq = seqs[seq];
+    const SsmScanSeq sq = scan_seqs[stretch];
+    const void *init = init_ptrs && sq.init_seq >= 0 ? init_ptrs[sq.init_seq] : nullptr;
     const int tile_begin = sq.tile_begin;
     const int n_tiles = sq.tile_end - sq.tile_begin;
     if (n_tiles <= 0)
         return;  // empty sequence: the whole workgroup leaves before any barrier
+    // a stretch that another one continues leaves its last state in a carry slot: fp32, as the register image of the
+    // accumulators ([head][block of 32 channels][block of 32 state indices][a][lane] float4), which the kernel that
+    // uses it reads back with contiguous wave loads
+    const bool carries = carry && sq.carry_out >= 0;
+    const rsrc_t carry_to = make_rsrc(
+        carry + (carries ? (size_t)sq.carry_out * H * P * kN + ((size_t)h * (P / 32) + pbase / 32) * (16 * 64 * 4) : 0),
+        carries ? NC * 16 * 1024 : 0);
 
     WaveLdsT<NC> &W = L.wv[w];
     const int i = lane & 31, q = lane >> 5;
@@ -545,6 +553,8 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
             const float ell2 = wave_inclusive_sum(dtj * Ah) * kLog2e;
             const float last = read_lane(ell2, 63), e31 = read_lane(ell2, 31);
             dl = exp2_fast(last);   // padded tokens have dt = 0, so this is e^{l_len}
+            if (tile_decay && lane == 0)
+                tile_decay[(size_t)h * n_tiles_all + tile_idx] = last;  // head-major: a head's tiles side by side
             fast = last > -100.f;   // 2^+-100 is far inside the fp32 range: the two-factor form of the decay is safe
             W.ell2[lane] = ell2;
             W.cj[lane] = ell2 - __builtin_amdgcn_logf(dtj);
@@ -625,6 +635,11 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
 #pragma unroll
                     for (int a = 0; a < 4; ++a)
                         store_state4(state_out, slot_row + 8 * a, sn[a], ST);
+                }
+                if (carries && k == n_tiles - 1) {
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+                        buf_store16(carry_to, lane16, ((c * 4 + nb) * 4 + a) * 1024, __builtin_bit_cast(uint4, sn[a]));
                 }
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf)
@@ -753,10 +768,222 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
     }
 }
 
+
+// ================================================================ sequences cut into stretches: the carried states
+// A later stretch of a cut sequence was scanned from a zero state.  The recurrence is linear in the state, so what is
+// missing is, for token t of the stretch, C_t applied to the state S the stretch truly starts from, decayed from the
+// stretch's start to t; for a checkpoint after t the decayed S itself.  S is the state its predecessor ended with (in
+// its carry slot, where the scan left it, completed by ssm_carry_kernel when the predecessor is itself a later
+// stretch).  The decay only shrinks along the stretch: once it is below 2^-150 nothing is added in fp32 and the rest
+// of the stretch is left alone, which for decay rates as trained models have them is all but its first few tiles.
+constexpr int kFixThreads = 256;
+#ifndef SSM_FIX_TILES_PER_STRETCH
+#define SSM_FIX_TILES_PER_STRETCH 96
+#endif
+constexpr int kFixTilesPerStretch = SSM_FIX_TILES_PER_STRETCH;  // waves per (later stretch, head, 64 channels), a tile each; the last goes on
+constexpr float kFixCutoffLog2 = -150.f;
+
+constexpr int LDYT = 64 + 4;  // row stride (floats) of a wave's tile of contributions: 32 tokens x 64 channels
+struct FixLds {
+    float ell2[kFixThreads / 64][kQ];
+    float yt[kFixThreads / 64][32][LDYT];
+};
+struct CarryLds {
+    float red[kFixThreads / 64];
+};
+
+// Turns the carry slots of a sequence cut into three or more stretches into true states: the slot a later stretch
+// filled holds what that stretch adds from zero; the state it starts from, decayed over the stretch, is added, one
+// stretch after the other.  One workgroup per (carry slot, head); only the one of a sequence's first slot works.
+__global__ __launch_bounds__(kFixThreads) void ssm_carry_kernel(float *__restrict__ carry,
+                                                                const float *__restrict__ tile_decay,
+                                                                const SsmScanSeq *__restrict__ scan_seqs, int H, int P,
+                                                                int n_tiles_all)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    CarryLds &L = *reinterpret_cast<CarryLds *>(lds_raw);
+    const int c = blockIdx.x / H, h = blockIdx.x % H;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int st = scan_seqs[c].of_slot;           // the stretch that starts from slot c
+    if (scan_seqs[st - 1].carry_in >= 0)
+        return;                              // not the first later stretch of its sequence
+    const size_t hpn = (size_t)H * P * kN, head = (size_t)h * P * kN;
+    for (; scan_seqs[st].carry_out >= 0; ++st) {
+        const SsmScanSeq sq = scan_seqs[st];
+        float part = 0.f;
+        for (int t = sq.tile_begin + tid; t < sq.tile_end; t += kFixThreads)
+            part += tile_decay[(size_t)h * n_tiles_all + t];
+        part = read_lane(wave_inclusive_sum(part), 63);
+        lds_barrier();  // the previous round has read the partial sums
+        if (lane == 0)
+            L.red[w] = part;
+        lds_barrier();
+        const float f = exp2_fast(L.red[0] + L.red[1] + L.red[2] + L.red[3]);
+        const float *in = carry + (size_t)sq.carry_in * hpn + head;
+        float *out = carry + (size_t)sq.carry_out * hpn + head;
+        for (int idx = 4 * tid; idx < P * kN; idx += 4 * kFixThreads) {
+            const float4 a = *reinterpret_cast<const float4 *>(in + idx);
+            float4 b = *reinterpret_cast<float4 *>(out + idx);
+            b.x = __builtin_fmaf(f, a.x, b.x);
+            b.y = __builtin_fmaf(f, a.y, b.y);
+            b.z = __builtin_fmaf(f, a.z, b.z);
+            b.w = __builtin_fmaf(f, a.w, b.w);
+            *reinterpret_cast<float4 *>(out + idx) = b;
+        }
+    }
+}
+
+// One wave per (carry slot, head, 64 channels, tile j < per_stretch of the stretch that starts from the slot), four
+// waves to a workgroup; a wave leaves at once where the decay is below the cutoff.  The wave of the last j goes on
+// tile after tile while the decay is above it.  No workgroup barrier anywhere: waves come and go on their own.
+template <int ST>
+__global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
+    bf16_t *__restrict__ y, void *__restrict__ state_out, const float *__restrict__ carry,
+    const float *__restrict__ tile_decay, const uint4 *__restrict__ frags, const bf16_t *__restrict__ dt_t,
+    const float *__restrict__ A_, const SsmTile *__restrict__ tiles, const SsmScanSeq *__restrict__ scan_seqs, int H,
+    int P, int G, int per_stretch, int n_tiles_all)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    FixLds &L = *reinterpret_cast<FixLds *>(lds_raw);
+    const int slices = P / 64, groups = (per_stretch + 3) / 4;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int b = blockIdx.x;
+    const int j = 4 * (b % groups) + w;
+    b /= groups;
+    const int slice = b % slices;
+    b /= slices;
+    const int h = b % H, c = b / H;
+    const SsmScanSeq sq = scan_seqs[scan_seqs[c].of_slot];
+    const int n_tiles = sq.tile_end - sq.tile_begin;
+    if (j >= n_tiles || j >= per_stretch)
+        return;
+    const int i = lane & 31, q = lane >> 5;
+    const int g = h / (H / G);
+    const float Ah = A_[h];
+
+    // decay from the stretch's start to the start of tile j
+    float cum;
+    {
+        float part = 0.f;
+        for (int k = lane; k < j; k += 64)
+            part += tile_decay[(size_t)h * n_tiles_all + sq.tile_begin + k];
+        cum = read_lane(wave_inclusive_sum(part), 63);
+    }
+    if (cum < kFixCutoffLog2)
+        return;
+
+    // the carried state of the 64 channels as fp16 operands, in the order the scan uses for S.C; the slot holds the
+    // register image the scan left: [head][block of 32 channels][block of 32 state indices][a][lane] float4
+    const size_t state_row = ((size_t)h * P + 64 * slice + i) * kN + 4 * q;  // + 32 cc kN: channel half cc
+    const float4 *S = reinterpret_cast<const float4 *>(carry + (size_t)c * H * P * kN) +
+                      ((size_t)h * (P / 32) + 2 * slice) * (16 * 64) + lane;
+    uint4 s16[2][4][2];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const float4 lo = S[((cc * 4 + nb) * 4 + 2 * hf) * 64], hi = S[((cc * 4 + nb) * 4 + 2 * hf + 1) * 64];
+                s16[cc][nb][hf] = make_uint4(pack2_f16(lo.x, lo.y), pack2_f16(lo.z, lo.w), pack2_f16(hi.x, hi.y),
+                                             pack2_f16(hi.z, hi.w));
+            }
+    const int yrow = lane >> 3, ycol = 8 * (lane & 7);  // rows of y: 8 lanes x 16 bytes, 8 rows per wave instruction
+    const uint32_t lane16 = lane * 16;
+    for (int jj = j;;) {
+        const int tile_idx = sq.tile_begin + jj;
+        const SsmTile t = tiles[tile_idx];
+        const rsrc_t img = make_rsrc(reinterpret_cast<const unsigned char *>(frags) +
+                                         ((size_t)tile_idx * G + g) * kMfmaTileGroupBytes,
+                                     kMfmaTileGroupBytes);
+        // per token half: C operands and y as it stands (whole 128-byte rows; rows past the end of a partial tile
+        // re-read its last row); the loads of the second half are issued before the first half's y is updated
+        uint4 cfr[8], yo[2][4];
+        auto issue_loads = [&](int ih) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                cfr[ks] = buf_load16(img, lane16, (ih * 8 + ks) * 1024);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int tok = 32 * ih + 8 * m + yrow < t.len ? 32 * ih + 8 * m + yrow : t.len - 1;
+                yo[ih][m] = *reinterpret_cast<const uint4 *>(y + ((size_t)(t.tok0 + tok) * H + h) * P + 64 * slice + ycol);
+            }
+        };
+        // element r of an accumulator: channel 32 cc + 8 (r / 4) + 4 q + r % 4 of token 32 ih + i
+        auto contribution_to_lds = [&](float f) {
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                f32x16 acc = zero16();
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    acc = mfma_f16(s16[cc][ks >> 1][ks & 1], cfr[ks], acc);
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    *reinterpret_cast<float4 *>(&L.yt[w][i][32 * cc + 8 * a + 4 * q]) =
+                        make_float4(f * acc[4 * a + 0], f * acc[4 * a + 1], f * acc[4 * a + 2], f * acc[4 * a + 3]);
+            }
+            lds_wait();
+        };
+        auto update_y = [&](int ih) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float4 d0 = *reinterpret_cast<const float4 *>(&L.yt[w][8 * m + yrow][ycol]);
+                const float4 d1 = *reinterpret_cast<const float4 *>(&L.yt[w][8 * m + yrow][ycol + 4]);
+                const uint4 o = yo[ih][m];
+                if (32 * ih + 8 * m + yrow < t.len)
+                    *reinterpret_cast<uint4 *>(y + ((size_t)(t.tok0 + 32 * ih + 8 * m + yrow) * H + h) * P + 64 * slice + ycol) =
+                        make_uint4(pack2_bf16(bf16_lo(o.x) + d0.x, bf16_hi(o.x) + d0.y),
+                                   pack2_bf16(bf16_lo(o.y) + d0.z, bf16_hi(o.y) + d0.w),
+                                   pack2_bf16(bf16_lo(o.z) + d1.x, bf16_hi(o.z) + d1.y),
+                                   pack2_bf16(bf16_lo(o.w) + d1.z, bf16_hi(o.w) + d1.w));
+            }
+            lds_wait();  // the tile of contributions is rewritten next
+        };
+        issue_loads(0);
+        const float dtj = __uint_as_float((uint32_t)dt_t[((size_t)tile_idx * H + h) * kQ + lane] << 16);
+        phase_end();
+        const float ell2 = wave_inclusive_sum(dtj * Ah) * kLog2e;
+        const float last = read_lane(ell2, 63);
+        L.ell2[w][lane] = ell2;
+        lds_wait();
+        const float f0 = exp2_fast(cum + L.ell2[w][i]), f1 = exp2_fast(cum + L.ell2[w][32 + i]);
+        lds_wait();  // the row is rewritten in the next round
+        contribution_to_lds(f0);
+        phase_end();
+        issue_loads(1);
+        phase_end();
+        update_y(0);
+        contribution_to_lds(f1);
+        update_y(1);
+        cum += last;
+        if (t.ckpt_slot >= 0 && cum >= kFixCutoffLog2) {  // the state after the tile: + the decayed carried state
+            const float fs = exp2_fast(cum);
+            const size_t slot = (size_t)t.ckpt_slot * H * P * kN;
+#pragma unroll 1
+            for (int cn = 0; cn < 8; ++cn)  // rare, and kept small: not unrolled
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const int cc = cn >> 2, nb = cn & 3;
+                        const size_t idx = state_row + (size_t)32 * cc * kN + 32 * nb + 8 * a;
+                        const float4 sv = S[((cc * 4 + nb) * 4 + a) * 64];
+                        float4 v = load_state4(state_out, slot + idx, ST);
+                        v.x = __builtin_fmaf(fs, sv.x, v.x);
+                        v.y = __builtin_fmaf(fs, sv.y, v.y);
+                        v.z = __builtin_fmaf(fs, sv.z, v.z);
+                        v.w = __builtin_fmaf(fs, sv.w, v.w);
+                        store_state4(state_out, slot + idx, v, ST);
+                    }
+        }
+        if (j != per_stretch - 1 || ++jj >= n_tiles || cum < kFixCutoffLog2)
+            break;
+    }
+}
+
 // NC channel halves of 32 per workgroup, NW waves.
 template <int ST, int NC, int NW>
 hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
-                          hipStream_t stream)
+                          float *tile_decay, float *carry, hipStream_t stream)
 {
     static std::once_flag attr_once[64];
     static hipError_t attr_err[64];
@@ -777,20 +1004,29 @@ hipError_t launch_scan_st(const ssm_plan *plan, const ScanArgs &args, const uint
         return hipSuccess;  // every sequence is empty
     hipLaunchKernelGGL((ssm_scan_mfma_kernel<ST, NC, NW>), dim3((unsigned)ssm_launch_blocks(plan->n_items)), dim3(64 * NW), lds,
                        stream, static_cast<const bf16_t *>(args.x), args.A, args.D, static_cast<bf16_t *>(args.y),
-                       args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.seqs, args.H, args.P, args.G,
-                       args.p_split, plan->n_items);
+                       args.state_out, args.init_ptrs, frags, dt_t, args.tiles, args.scan_seqs, tile_decay, carry, args.H,
+                       args.P, args.G, args.p_split, plan->n_items, (int)plan->tiles.size());
     return hipGetLastError();
 }
 
 template <int NC, int NW>
 hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const uint4 *frags, const bf16_t *dt_t,
-                             hipStream_t stream)
+                             float *tile_decay, float *carry, hipStream_t stream)
 {
     switch (args.state_dtype) {
-    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16, NC, NW>(plan, args, frags, dt_t, stream);
-    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16, NC, NW>(plan, args, frags, dt_t, stream);
-    default: return launch_scan_st<SSM_ST_F32, NC, NW>(plan, args, frags, dt_t, stream);
+    case SSM_ST_F16: return launch_scan_st<SSM_ST_F16, NC, NW>(plan, args, frags, dt_t, tile_decay, carry, stream);
+    case SSM_ST_BF16: return launch_scan_st<SSM_ST_BF16, NC, NW>(plan, args, frags, dt_t, tile_decay, carry, stream);
+    default: return launch_scan_st<SSM_ST_F32, NC, NW>(plan, args, frags, dt_t, tile_decay, carry, stream);
     }
+}
+
+template <int ST>
+void launch_fix_st(const ScanArgs &args, const float *carry, const float *tile_decay, const uint4 *frags,
+                   const bf16_t *dt_t, unsigned blocks, int per_stretch, int n_tiles_all, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ssm_fix_kernel<ST>, dim3(blocks), dim3(kFixThreads), sizeof(FixLds), stream,
+                       static_cast<bf16_t *>(args.y), args.state_out, carry, tile_decay, frags, dt_t, args.A, args.tiles,
+                       args.scan_seqs, args.H, args.P, args.G, per_stretch, n_tiles_all);
 }
 
 }  // namespace
@@ -798,11 +1034,14 @@ hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const u
 hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *workspace, hipStream_t stream)
 {
     const int n_tiles = (int)plan->tiles.size();
-    if (n_tiles == 0 || plan->n_workgroups == 0)
+    if (n_tiles == 0 || plan->n_items == 0)
         return hipSuccess;
-    uint4 *frags = static_cast<uint4 *>(workspace);
-    bf16_t *dt_t = reinterpret_cast<bf16_t *>(static_cast<unsigned char *>(workspace) +
-                                              (size_t)n_tiles * args.G * kMfmaTileGroupBytes);
+    const SsmMfmaWorkspace ws = ssm_mfma_workspace(plan);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    uint4 *frags = reinterpret_cast<uint4 *>(base + ws.images);
+    bf16_t *dt_t = reinterpret_cast<bf16_t *>(base + ws.dt_rows);
+    float *tile_decay = plan->n_carry > 0 ? reinterpret_cast<float *>(base + ws.tile_decay) : nullptr;
+    float *carry = plan->n_carry > 0 ? reinterpret_cast<float *>(base + ws.carry) : nullptr;
     // few (tile, group) pairs: four workgroups each, so that the preparation does not run on a corner of the GPU
     const int parts = (long long)n_tiles * args.G < kMfmaPrepSplitBelow ? 4 : 1;
     hipLaunchKernelGGL(ssm_prep_kernel, dim3((unsigned)n_tiles * (unsigned)args.G * (unsigned)parts), dim3(kPrepThreads),
@@ -811,12 +1050,39 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
-    if (hipEvent_t mark = ssm_profile_event()) {
+    if (hipEvent_t mark = ssm_profile_event(0)) {
         e = hipEventRecord(mark, stream);
         if (e != hipSuccess)
             return e;
     }
     if (args.P / args.p_split == 64)
-        return launch_scan_width<2, kWavesWide>(plan, args, frags, dt_t, stream);
-    return launch_scan_width<1, kWavesNarrow>(plan, args, frags, dt_t, stream);
+        e = launch_scan_width<2, kWavesWide>(plan, args, frags, dt_t, tile_decay, carry, stream);
+    else
+        e = launch_scan_width<1, kWavesNarrow>(plan, args, frags, dt_t, tile_decay, carry, stream);
+    if (e != hipSuccess)
+        return e;
+    if (hipEvent_t mark = ssm_profile_event(1)) {
+        e = hipEventRecord(mark, stream);
+        if (e != hipSuccess)
+            return e;
+    }
+    if (plan->n_carry == 0)
+        return hipSuccess;
+    // sequences cut into stretches: complete the carried states (three or more stretches), then add what they
+    // contribute to the later stretches
+    if (plan->carry_chains) {
+        hipLaunchKernelGGL(ssm_carry_kernel, dim3((unsigned)plan->n_carry * (unsigned)args.H), dim3(kFixThreads),
+                           sizeof(CarryLds), stream, carry, tile_decay, args.scan_seqs, args.H, args.P, n_tiles);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    const int per_stretch = plan->max_later_tiles < kFixTilesPerStretch ? plan->max_later_tiles : kFixTilesPerStretch;
+    const unsigned blocks =
+        (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) * (unsigned)((per_stretch + 3) / 4);
+    switch (args.state_dtype) {
+    case SSM_ST_F16: launch_fix_st<SSM_ST_F16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
+    case SSM_ST_BF16: launch_fix_st<SSM_ST_BF16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
+    default: launch_fix_st<SSM_ST_F32>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
+    }
+    return hipGetLastError();
 }

@@ -1,7 +1,7 @@
-// Spot check of the matrix-core scan kernel at full problem sizes on the emulator (test infrastructure only): only
-// the first two and the last workgroup of the scan run (and the workgroups of the kernel in front of it that they
-// depend on), every buffer is guarded, and the outputs of those workgroups are compared with a plain fp64 recurrence
-// computed here.  Inputs are drawn only where those workgroups read them.   emu_big <T> <ckpt_every> [H P G]
+// Spot check of the matrix-core scan at full problem sizes on the emulator (test infrastructure only): only the
+// workgroups of the first two heads and of the last head run (in the scan, in the kernel in front of it, and in the
+// kernels behind it that handle sequences cut into stretches), every buffer is guarded, and the outputs for those
+// heads are compared with a plain fp64 recurrence computed here.  Inputs are drawn only where those workgroups read them.   emu_big <T> <ckpt_every> [H P G]
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <cstdio>
@@ -11,18 +11,24 @@
 #include "emu_host.h"
 namespace emu { void set_order_mode(int m); void set_block_filter(bool (*)(int, unsigned)); long switches(); }
 
-static int gH, gP, gG, g_psplit, g_items, g_prep_parts = 1;
-static std::vector<int> g_wgs;   // logical workgroup ids to run
+static int gH, gP, gG, g_psplit, g_items, g_prep_parts = 1, g_fix_per_stretch = 1, g_launches_before_fix = 2;
+static std::vector<int> g_heads;  // heads whose workgroups run
+static bool has_head(int h) { for (int x : g_heads) if (x == h) return true; return false; }
 static bool filter(int launch, unsigned b)
 {
     if (launch == 0) {  // the kernel in front of the scan, one or four blocks per (tile, group): keep the groups of the selected heads
         const int g = (b / g_prep_parts) % gG;  // block = ((tile * G) + g) * parts + part
-        for (int wg : g_wgs) if (((wg / g_psplit) % gH) / (gH / gG) == g) return true;
+        for (int h : g_heads) if (h / (gH / gG) == g) return true;
         return false;
     }
-    const int wg = ssm_launch_item(b, g_items);  // one sequence: item = (head, slice)
-    for (int w : g_wgs) if (w == wg) return true;
-    return false;
+    if (launch == 1) {  // the scan: item = ((rank of the stretch) * H + head) * slices + slice
+        const int item = ssm_launch_item(b, g_items);
+        return item >= 0 && has_head((item / g_psplit) % gH);
+    }
+    if (launch < g_launches_before_fix)  // completing the carried states: block = slot * H + head
+        return has_head(b % gH);
+    // adding the carried states' contribution: block = ((slot * H + head) * slices + slice) * groups of 4 tiles + group
+    return has_head((b / ((g_fix_per_stretch + 3) / 4) / (gP / 64)) % gH);
 }
 static uint32_t hash32(uint64_t x) { x ^= x >> 33; x *= 0xff51afd7ed558ccdULL; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ULL; x ^= x >> 33; return (uint32_t)x; }
 static float unif(uint64_t k) { return (hash32(k) >> 8) * (1.0f / 16777216.0f); }
@@ -38,16 +44,19 @@ int main(int argc, char **argv)
     ssm_plan_t *plan; if (ssm_plan_create(&sh, 1, cu, cuck, ck.data(), &plan)) { printf("plan: %s\n", ssm_last_error()); return 1; }
     g_psplit = plan->p_split; g_items = plan->n_items;
     g_prep_parts = (long long)plan->tiles.size() * G < kMfmaPrepSplitBelow ? 4 : 1;
-    g_wgs = {0, 1, plan->n_workgroups - 1};
+    g_fix_per_stretch = plan->max_later_tiles < 96 ? (plan->max_later_tiles > 0 ? plan->max_later_tiles : 1) : 96;
+    g_launches_before_fix = plan->carry_chains ? 3 : 2;
+    g_heads = {0, 1, H - 1};
     const size_t nx = (size_t)T * H * P, nb = (size_t)T * G * N, ndt = (size_t)T * H, nst = (size_t)H * P * N;
-    printf("T=%d tiles=%zu wgs=%d ckpts=%zu; x %.2f GB\n", T, plan->tiles.size(), plan->n_workgroups, ck.size(), nx * 2 / 1e9);
+    printf("T=%d tiles=%zu wgs=%d stretches=%zu ckpts=%zu; x %.2f GB\n", T, plan->tiles.size(), plan->n_workgroups,
+           plan->scan_seqs.size(), ck.size(), nx * 2 / 1e9);
     bf16_t *x = (bf16_t *)guarded(nx * 2, true), *y = (bf16_t *)guarded(nx * 2, true), *B = (bf16_t *)guarded(nb * 2, true),
            *C = (bf16_t *)guarded(nb * 2, true), *dt = (bf16_t *)guarded(ndt * 2, true);
     float *A = (float *)guarded(H * 4, true), *D = (float *)guarded(H * 4, true);
     float *st = (float *)guarded((ck.size() ? ck.size() : 1) * nst * 4, true);
     // inputs only where the selected workgroups read them (the rest stays zero: untouched pages cost nothing)
-    std::vector<int> heads, groups;
-    for (int wg : g_wgs) { int h = (wg / g_psplit) % H; heads.push_back(h); groups.push_back(h / (H / G)); }
+    std::vector<int> heads = g_heads, groups;
+    for (int h : heads) groups.push_back(h / (H / G));
     for (int h = 0; h < H; ++h) { A[h] = -expf(unif(7000 + h) * logf(16.f)); D[h] = unif(8000 + h) * 2 - 1; }
     for (int t = 0; t < T; ++t) {
         for (int h : heads) {
@@ -62,16 +71,19 @@ int main(int argc, char **argv)
     SsmTile *tiles = (SsmTile *)guarded(plan->tiles.size() * sizeof(SsmTile), true);
     SsmSeq *seqs = (SsmSeq *)guarded(sizeof(SsmSeq), true);
     memcpy(tiles, plan->tiles.data(), plan->tiles.size() * sizeof(SsmTile)); memcpy(seqs, plan->seqs.data(), sizeof(SsmSeq));
+    SsmScanSeq *scan_seqs = (SsmScanSeq *)guarded(plan->scan_seqs.size() * sizeof(SsmScanSeq), true);
+    memcpy(scan_seqs, plan->scan_seqs.data(), plan->scan_seqs.size() * sizeof(SsmScanSeq));
     ScanArgs a; a.x = x; a.dt = dt; a.A = A; a.B = B; a.C = C; a.D = D; a.y = y; a.state_out = st; a.init_ptrs = nullptr;
-    a.tiles = tiles; a.seqs = seqs; a.H = H; a.P = P; a.N = N; a.G = G; a.p_split = plan->p_split; a.state_dtype = SSM_ST_F32;
+    a.tiles = tiles; a.seqs = seqs; a.scan_seqs = scan_seqs; a.H = H; a.P = P; a.N = N; a.G = G; a.p_split = plan->p_split; a.state_dtype = SSM_ST_F32;
     emu::set_order_mode(1); emu::set_block_filter(filter);
     size_t ws_bytes = 0; ssm_plan_workspace_bytes(plan, &ws_bytes);
     void *ws = guarded(ws_bytes ? ws_bytes : 16, true);
     if (launch_scan_mfma(plan, a, ws, nullptr) != hipSuccess) { printf("launch failed\n"); return 1; }
-    printf("emulated %zu workgroups, %ld fiber switches\n", g_wgs.size(), emu::switches());
+    printf("emulated the workgroups of %zu heads, %ld fiber switches\n", g_heads.size(), emu::switches());
     double worst_y = 0, worst_s = 0;
-    for (int wg : g_wgs) {
-        const int h = (wg / g_psplit) % H, ps = wg % g_psplit, g = h / (H / G), p0 = ps * 32;
+    const int NP = 32;  // channels checked per head: the first 32 of its last slice
+    for (int h : g_heads) {
+        const int ps = g_psplit - 1, g = h / (H / G), p0 = ps * (P / g_psplit);
         std::vector<double> S(32 * (size_t)N, 0.0), ref((size_t)T * 32);
         double rms = 0; size_t k = 0; double es = 0, srms = 0; std::vector<double> sref;
         for (int t = 0; t < T; ++t) {
@@ -92,7 +104,7 @@ int main(int argc, char **argv)
         rms = sqrt(rms / ((double)T * 32)); double ey = 0;
         for (int t = 0; t < T; ++t) for (int p = 0; p < 32; ++p) { const double r = ref[(size_t)t * 32 + p], gq = bf16_to_f32(y[((size_t)t * H + h) * P + p0 + p]);
             const double e = fabs(gq - r) / fmax(fabs(r), rms); if (!(e <= ey)) ey = e; }
-        printf("wg %d (head %d, slice %d): y err %.3e, state err %.3e over %zu checkpoints\n", wg, h, ps, ey, es, k);
+        printf("head %d, channels %d..%d: y err %.3e, state err %.3e over %zu checkpoints\n", h, p0, p0 + NP - 1, ey, es, k);
         if (!(ey <= worst_y)) worst_y = ey; if (!(es <= worst_s)) worst_s = es;
     }
     printf(worst_y <= 2e-2 && worst_s <= 2e-2 ? "BIG CHECK OK\n" : "BIG CHECK FAILED\n");

@@ -32,4 +32,4 @@ template <typename T> static void read_vec(FILE *f, T *dst, size_t n)
 
 
 // The launchers ask the library for the profiling event of the calling thread; the emulation has none.
-void *ssm_profile_event() { return nullptr; }
+void *ssm_profile_event(int) { return nullptr; }

@@ -103,15 +103,29 @@ int main(int argc, char **argv)
     }
     if (getenv("EMU_WIDE") && plan->path == SSM_PATH_MFMA_BF16 && P % kMfmaWideChannels == 0) {
         // the 64-channel variant of the matrix-core scan, which the plan itself picks only for grids that fill a GPU
-        plan->p_split = P / kMfmaWideChannels;
-        plan->n_workgroups = batch * H * plan->p_split;
-        ssm_plan_order_sequences(plan);
+        ssm_plan_build_stretches(plan, 1, 0);
+    }
+    if (const char *sp = getenv("EMU_SPLIT")) {
+        // "K:min": sequences cut into up to K stretches of at least `min` tiles (the plan itself cuts only long
+        // sequences of batches that would leave a GPU idle)
+        int kk = 2, min_tiles = 1;
+        sscanf(sp, "%d:%d", &kk, &min_tiles);
+        if (plan->path == SSM_PATH_MFMA_BF16 && P % kMfmaWideChannels == 0) {
+            int active = 0;
+            for (int b = 0; b < batch; ++b)
+                active += cu[b + 1] > cu[b];
+            ssm_plan_build_stretches(plan, (int64_t)active * H * (P / kMfmaWideChannels) * kk, min_tiles);
+            fprintf(stderr, "stretches: %zu, carry slots: %d\n", plan->scan_seqs.size(), plan->n_carry);
+        }
     }
     const size_t nt = plan->tiles.size();
     SsmTile *tiles = static_cast<SsmTile *>(guarded(sizeof(SsmTile) * (nt ? nt : 1), end_aligned));
     SsmSeq *seqs = static_cast<SsmSeq *>(guarded(sizeof(SsmSeq) * (batch ? batch : 1), end_aligned));
     memcpy(tiles, plan->tiles.data(), sizeof(SsmTile) * nt);
     memcpy(seqs, plan->seqs.data(), sizeof(SsmSeq) * batch);
+    const size_t nss = plan->scan_seqs.size();
+    SsmScanSeq *scan_seqs = static_cast<SsmScanSeq *>(guarded(sizeof(SsmScanSeq) * (nss ? nss : 1), end_aligned));
+    memcpy(scan_seqs, plan->scan_seqs.data(), sizeof(SsmScanSeq) * nss);
 
     void *y = guarded((nx ? nx : 1) * esz, end_aligned);
     float *st = static_cast<float *>(guarded((size_t)(n_ckpt ? n_ckpt : 1) * nst * 4, end_aligned));
@@ -121,7 +135,7 @@ int main(int argc, char **argv)
     ScanArgs args;
     args.x = x, args.dt = dt, args.A = A, args.B = B, args.C = C, args.D = D, args.y = y, args.state_out = st;
     args.init_ptrs = any_init ? reinterpret_cast<const void *const *>(init) : nullptr;
-    args.tiles = tiles, args.seqs = seqs;
+    args.tiles = tiles, args.seqs = seqs, args.scan_seqs = scan_seqs;
     args.H = H, args.P = P, args.N = N, args.G = G, args.p_split = plan->p_split;
     args.state_dtype = st_type;
     if (advance) {

@@ -213,10 +213,10 @@ def test_misaligned_and_null_pointers_are_rejected():
     plan.close()
 
 
-def test_profile_mark_event_sits_between_the_two_kernels():
-    """ssm_profile_mark: the event handed over is recorded on the call's stream after the operand preparation and
-    before the scan, so start -> mark and mark -> end are both positive and add up to the call; switching it off
-    leaves a later call's timing events alone."""
+def test_profile_mark_events_sit_between_the_kernels():
+    """ssm_profile_mark: the events handed over are recorded on the call's stream after the operand preparation and
+    after the scan, so start -> first, first -> second are positive and, with what follows the second, add up to the
+    call; switching them off leaves a later call's timing events alone."""
     import paper_2411_19379_amd as ssm
     say("profile mark: event between the two kernels of the matrix-core scan")
     shape = LayerShape(8, 64, 128, 2, 256, "bf16")
@@ -224,20 +224,21 @@ def test_profile_mark_event_sits_between_the_two_kernels():
     plan = ssm.Plan(shape.nheads, shape.headdim, shape.d_state, shape.ngroups, shape.chunk, "bf16", wl.cu_seqlens,
                     wl.ckpt_pos)
     inp = wl.inputs
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for e in ev:
         e.record()  # creates the HIP events
     y_ref, st_ref = ssm.prefill(plan, inp.x, inp.dt, wl.A, inp.B, inp.C, wl.D)
     torch.cuda.synchronize()
     ev[0].record()
-    ssm.ssm_profile_mark(ev[1].cuda_event)
+    ssm.ssm_profile_mark(ev[1].cuda_event, ev[2].cuda_event)
     y, st = ssm.prefill(plan, inp.x, inp.dt, wl.A, inp.B, inp.C, wl.D)
-    ev[2].record()
-    ssm.ssm_profile_mark(None)
+    ev[3].record()
+    ssm.ssm_profile_mark(None, None)
     torch.cuda.synchronize()
-    prep, scan, call = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[0].elapsed_time(ev[2])
-    say(f"    prep {prep * 1e3:.1f} us, scan {scan * 1e3:.1f} us, call {call * 1e3:.1f} us")
-    assert prep > 0 and scan > 0 and abs(prep + scan - call) <= 0.05 * call + 0.01
+    prep, scan, rest = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), ev[2].elapsed_time(ev[3])
+    call = ev[0].elapsed_time(ev[3])
+    say(f"    prep {prep * 1e3:.1f} us, scan {scan * 1e3:.1f} us, after it {rest * 1e3:.1f} us, call {call * 1e3:.1f} us")
+    assert prep > 0 and scan > 0 and rest >= 0 and abs(prep + scan + rest - call) <= 0.05 * call + 0.01
     assert torch.equal(y, y_ref) and torch.equal(st, st_ref), "the mark must not change results"
     plan.close()
 

@@ -98,7 +98,7 @@ def emu_binary(tmp_path_factory):
 @pytest.fixture(scope="session")
 def emu_binary_4waves(tmp_path_factory):
     """The matrix-core scan with 4 waves per workgroup instead of the shipped 12 (32 channels) or 8 (64 channels)."""
-    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4", "-DSSM_SCAN_WAVES_NARROW=4"])
+    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4", "-DSSM_SCAN_WAVES_NARROW=4", "-DSSM_FIX_TILES_PER_STRETCH=2"])
 
 
 @pytest.fixture(scope="session")
@@ -152,8 +152,10 @@ def _read_result(path, wl, n_states=None):
     return y.reshape(wl.total_tokens, s.nheads, s.headdim), st, raw
 
 
-def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False, state_type=None, wide=False):
-    pin, pout = str(tmp_path / "in.bin"), str(tmp_path / f"out_{order}_{align}_{drop}_{advance}_{state_type}_{wide}.bin")
+def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False, state_type=None, wide=False,
+             split=None):
+    pin = str(tmp_path / "in.bin")
+    pout = str(tmp_path / f"out_{order}_{align}_{drop}_{advance}_{state_type}_{wide}_{split}.bin".replace(":", "-"))
     if not os.path.exists(pin):
         _write_problem(pin, wl, init)
     cmd = [binary, pin, pout, str(order), align]
@@ -164,6 +166,8 @@ def _emulate(binary, wl, init, tmp_path, order, align, drop=None, advance=False,
         if state_type:
             cmd.append(state_type)
     env = dict(os.environ, EMU_WIDE="1") if wide else None  # the 64-channel variant of the matrix-core scan
+    if split:  # "K:min": sequences cut into up to K stretches of at least `min` tiles
+        env = dict(os.environ, EMU_SPLIT=split)
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=300, env=env)
     assert r.returncode == 0, f"emulated kernel died (rc {r.returncode}): {r.stderr[-800:]}"
     return _read_result(pout, wl, n_states=wl.batch if advance else None)
@@ -208,7 +212,7 @@ CASES = {
 }
 
 
-def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None, wide=False):
+def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None, wide=False, split=None):
     (H, P, N, G, chunk), cfg, kw = CASES[case]
     if io == "f32" and P * N > 8192:
         pytest.skip("the fp32 vector kernel holds at most 8192 state elements per head")
@@ -224,7 +228,7 @@ def _check_case(binary, tmp_path, io, case, state_tol=None, y_tol=None, wide=Fal
     y_ref, st_ref = _oracle(wl, init)
     first = None
     for order, align in ((0, "end"), (1, "start"), (7, "end"), (12, "start")):
-        y, st, raw = _emulate(binary, wl, init, tmp_path, order, align, wide=wide)
+        y, st, raw = _emulate(binary, wl, init, tmp_path, order, align, wide=wide, split=split)
         assert np.all(np.isfinite(y)) and np.all(np.isfinite(st)), "an output was never written, or LDS was read before written"
         assert max(rel_err(y, y_ref)) <= (y_tol or TOL[io])
         assert max(rel_err(st.astype(np.float64), st_ref)) <= (state_tol or TOL[io])
@@ -409,6 +413,26 @@ def test_emulated_64_channel_scan_matches_oracle_in_any_wave_order(emu_binary, t
     """The variant of the matrix-core scan whose workgroups own 64 channels (the plan picks it for grids that fill a
     GPU; the emulation driver forces it): same checks as for the 32-channel kernel."""
     _check_case(emu_binary, tmp_path, "bf16", case, wide=True)
+
+
+@pytest.mark.parametrize("split", ["2:1", "3:1", "5:2"])
+@pytest.mark.parametrize("case", ["ragged", "long", "tiny", "p128", "empty_seq", "strong_decay", "heads7"])
+def test_emulated_scan_of_sequences_cut_into_stretches_matches_oracle(emu_binary, tmp_path, case, split):
+    """Sequences cut into stretches that are scanned at the same time, the later ones from a zero state, and the
+    kernels that carry the states over and add their contribution (the plan cuts only long sequences of batches that
+    would leave a GPU idle; the emulation driver forces it on small ones): same checks as for the uncut scan.  Covers
+    two stretches, chains of three and more, stretches of a single tile, checkpoints and cached initial states in
+    any stretch, and decay so strong that the carried state adds nothing."""
+    if CASES[case][0][1] % 64:
+        pytest.skip("sequences are cut only where workgroups own 64 channels")
+    _check_case(emu_binary, tmp_path, "bf16", case, split=split)
+
+
+@pytest.mark.parametrize("case", ["ragged", "long"])
+def test_emulated_stretches_with_one_workgroup_for_many_tiles(emu_binary_4waves, tmp_path, case):
+    """As above, built so that a stretch gets at most two workgroups in the second kernel: the last one walks on
+    through the remaining tiles."""
+    _check_case(emu_binary_4waves, tmp_path, "bf16", case, split="2:1")
 
 
 @pytest.mark.parametrize("order", [0, 1, 9])

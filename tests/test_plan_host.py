@@ -19,6 +19,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ssm_[a-z0-9_]+)\s*\(", header))
     assert names == {"ssm_plan_create", "ssm_plan_info", "ssm_plan_tile", "ssm_plan_launch_order", "ssm_plan_launch_item",
+                     "ssm_plan_stretch",
                      "ssm_plan_workspace_bytes",
                      "ssm_prefill", "ssm_prefill_noalloc", "ssm_state_advance", "ssm_conv1d_prefill",
                      "ssm_profile_mark", "ssm_plan_destroy", "ssm_last_error"}
@@ -163,15 +164,15 @@ def test_launch_order_covers_every_item_once_and_balances_the_dies():
         cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
         plan = ssm.Plan(H, P, 128, 1 if H == 80 else 2, 64, "bf16", cu.tolist(), None)
         by_length, slices, n_items, n_blocks = plan.launch_order()
-        tiles = np.zeros(batch, dtype=np.int64)
-        for (_, _, seq, _) in plan.tiles():
-            tiles[seq] += 1
-        assert sorted(by_length) == list(range(batch))
+        stretches = plan.stretches()
+        n_st = plan.info.n_stretches
+        tiles = np.asarray([e - b for b, e, _ in stretches], dtype=np.int64)
+        assert sorted(by_length) == list(range(n_st))
         ranked = tiles[by_length]
-        assert all(ranked[i] >= ranked[i + 1] for i in range(batch - 1))
-        assert all(by_length[i] < by_length[i + 1] for i in range(batch - 1) if ranked[i] == ranked[i + 1])
+        assert all(ranked[i] >= ranked[i + 1] for i in range(n_st - 1))
+        assert all(by_length[i] < by_length[i + 1] for i in range(n_st - 1) if ranked[i] == ranked[i + 1])
         per_seq = H * slices
-        assert slices in (P // 32, P // 64) and plan.info.n_workgroups == batch * per_seq
+        assert slices in (P // 32, P // 64) and plan.info.n_workgroups == n_st * per_seq
         assert n_items == int((tiles > 0).sum()) * per_seq
         assert n_blocks % 8 == 0 and n_items <= n_blocks < n_items + 256
         if n_items < 256:
@@ -192,3 +193,59 @@ def test_launch_order_covers_every_item_once_and_balances_the_dies():
         if n_items >= 1024:
             assert max(ends) <= 1.12 * weight[:n_items].sum() / 256 + weight.max() * 0.25, (ends, lens)
         plan.close()
+
+
+def test_long_sequences_of_small_batches_are_cut_into_stretches():
+    """A batch with fewer than 256 (sequence, head, 64-channel slice) streams: its long sequences are cut into
+    stretches of at least 64 tiles until there are 256, the stretches of a sequence partition its tiles in order, only
+    the first does not start from zero, and the workspace has room for one fp32 state per later stretch and one fp32
+    per (tile, head).  Batches that fill the GPU, short sequences and the fp32 path are left alone."""
+    def plan_of(lens, H=128, P=64, io="bf16", ckpt=None):
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        return ssm.Plan(H, P, 128, 8 if H % 8 == 0 else 1, 64, io, cu.tolist(), ckpt)
+
+    def check_partition(plan, lens):
+        per_seq = {}
+        for (_, _, seq, _) in plan.tiles():
+            per_seq[seq] = per_seq.get(seq, 0) + 1
+        st = plan.stretches()
+        pos, later = 0, 0
+        for i, n in enumerate((per_seq.get(i, 0) for i in range(len(lens)))):
+            mine = []
+            while pos < len(st) and (not mine or st[pos][2]):
+                if mine or not st[pos][2]:
+                    mine.append(st[pos])
+                    pos += 1
+            assert not mine[0][2] and all(z for _, _, z in mine[1:])
+            assert all(a[1] == b[0] for a, b in zip(mine, mine[1:]))
+            assert mine[-1][1] - mine[0][0] == n
+            later += len(mine) - 1
+        assert pos == len(st)
+        return later
+
+    p = plan_of([32768])  # 128 streams: two stretches of 256 tiles
+    assert p.info.n_stretches == 2 and p.stretches() == [(0, 256, False), (256, 512, True)]
+    assert check_partition(p, [32768]) == 1
+    assert p.info.n_workgroups == 2 * 128
+    base = 512 * (8 * 38912 + 128 * 128)
+    assert ssm.ssm_plan_workspace_bytes(p.handle) == base + 512 * 128 * 4 + 128 * 64 * 128 * 4
+    p.close()
+    p = plan_of([32768], H=32)  # 32 streams: 8 stretches of 64 tiles
+    assert p.info.n_stretches == 8 and check_partition(p, [32768]) == 7
+    p.close()
+    p = plan_of([32768], H=16)  # 16 streams: 8 stretches are the most, 128 streams in all: 32 channels per workgroup
+    assert p.info.n_stretches == 8 and p.info.n_workgroups == 8 * 16 * 2
+    p.close()
+    p = plan_of([2048], H=80)   # too short to cut
+    assert p.info.n_stretches == 1 and p.info.n_workgroups == 160
+    p.close()
+    p = plan_of([20000, 300, 0, 9000], H=40)  # 120 streams: cut in three where long enough, else two, else not
+    assert [e - b for b, e, _ in p.stretches()] == [104, 104, 105, 5, 0, 70, 71]
+    assert check_partition(p, [20000, 300, 0, 9000]) == 3
+    p.close()
+    p = plan_of([16384, 16384])  # 256 streams: nothing to cut
+    assert p.info.n_stretches == 2 and not any(z for _, _, z in p.stretches())
+    p.close()
+    p = plan_of([32768], H=8, io="f32")
+    assert p.info.n_stretches == 1
+    p.close()
