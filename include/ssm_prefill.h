@@ -209,7 +209,7 @@ int ssm_prefill(const ssm_plan_t *plan,
  *
  * Limits: at most 16384 tiles (ssm_plan_info n_tiles) and 1024 sequences per
  * call, otherwise SSM_ERR_UNSUPPORTED_SHAPE and nothing is enqueued.  The
- * array (280 KiB per GPU the library runs on, held until the process ends) is
+ * array (312 KiB per GPU the library runs on, held until the process ends) is
  * shared by every call on that GPU: calls that overlap on one GPU, on
  * different streams, race.  Calls on one stream are ordered by the stream.
  * Every call rewrites all it reads of the array, so nothing carries over from

@@ -616,38 +616,49 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
             for (int c = 0; c < NC; ++c)
                 asm volatile("" : "+v"(Sl[c]));
             wait_counter(&L.done[nb], k);
-            uint4 s16[NC][2];
+            // between one tile's hand-off and the next: read the block, multiply-add, write it back, publish.  What
+            // else needs the old or the new value (checkpoint, carry slot, the operand of S.C) comes after.
+            float4 sp[NC][4], sn[NC][4];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                float4 sp[4];
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
-                    sp[a] = L.S[c][nb][a][lane];
-                float4 sn[4];
+                    sp[c][a] = L.S[c][nb][a][lane];
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    sn[a] = make_float4(__builtin_fmaf(dl, sp[a].x, Sl[c][4 * a + 0]), __builtin_fmaf(dl, sp[a].y, Sl[c][4 * a + 1]),
-                                        __builtin_fmaf(dl, sp[a].z, Sl[c][4 * a + 2]), __builtin_fmaf(dl, sp[a].w, Sl[c][4 * a + 3]));
-                    L.S[c][nb][a][lane] = sn[a];
+                    sn[c][a] = make_float4(
+                        __builtin_fmaf(dl, sp[c][a].x, Sl[c][4 * a + 0]), __builtin_fmaf(dl, sp[c][a].y, Sl[c][4 * a + 1]),
+                        __builtin_fmaf(dl, sp[c][a].z, Sl[c][4 * a + 2]), __builtin_fmaf(dl, sp[c][a].w, Sl[c][4 * a + 3]));
+                    L.S[c][nb][a][lane] = sn[c][a];
                 }
-                if (t.ckpt_slot >= 0) {
+            publish_counter(&L.done[nb], k + 1, lane);
+            if (t.ckpt_slot >= 0) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
                     const size_t slot_row = (size_t)t.ckpt_slot * H * P * kN + state_row + (size_t)32 * c * kN + 32 * nb;
 #pragma unroll
                     for (int a = 0; a < 4; ++a)
-                        store_state4(state_out, slot_row + 8 * a, sn[a], ST);
+                        store_state4(state_out, slot_row + 8 * a, sn[c][a], ST);
                 }
-                if (carries && k == n_tiles - 1) {
+            }
+            if (carries && k == n_tiles - 1) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
 #pragma unroll
                     for (int a = 0; a < 4; ++a)
-                        buf_store16(carry_to, lane16, ((c * 4 + nb) * 4 + a) * 1024, __builtin_bit_cast(uint4, sn[a]));
-                }
+                        buf_store16(carry_to, lane16, ((c * 4 + nb) * 4 + a) * 1024, __builtin_bit_cast(uint4, sn[c][a]));
+            }
+            uint4 s16[NC][2];
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf)
-                    s16[c][hf] = make_uint4(pack2_f16(sp[2 * hf].x, sp[2 * hf].y), pack2_f16(sp[2 * hf].z, sp[2 * hf].w),
-                                            pack2_f16(sp[2 * hf + 1].x, sp[2 * hf + 1].y),
-                                            pack2_f16(sp[2 * hf + 1].z, sp[2 * hf + 1].w));
-            }
-            publish_counter(&L.done[nb], k + 1, lane);
+                    s16[c][hf] = make_uint4(pack2_f16(sp[c][2 * hf].x, sp[c][2 * hf].y),
+                                            pack2_f16(sp[c][2 * hf].z, sp[c][2 * hf].w),
+                                            pack2_f16(sp[c][2 * hf + 1].x, sp[c][2 * hf + 1].y),
+                                            pack2_f16(sp[c][2 * hf + 1].z, sp[c][2 * hf + 1].w));
             // S_s C_i over the 32 state indices of this block: two k-steps of 16
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
