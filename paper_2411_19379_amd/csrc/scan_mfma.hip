@@ -802,6 +802,14 @@ struct FixLds {
 struct CarryLds {
     float red[kFixThreads / 64];
 };
+// The tiles of the first later stretches, by carry slot, as a kernel argument: with few slots (the usual case: one
+// long sequence in two to four stretches) a wave of ssm_fix_kernel knows its stretch without a dependent chain of
+// loads from the stretch table in front of the one load it needs to decide whether it has work.
+constexpr int kFixSlotsInArgs = 8;
+struct FixSlots {
+    int32_t tile_begin[kFixSlotsInArgs];
+    int32_t tile_end[kFixSlotsInArgs];
+};
 
 // Turns the carry slots of a sequence cut into three or more stretches into true states: the slot a later stretch
 // filled holds what that stretch adds from zero; the state it starts from, decayed over the stretch, is added, one
@@ -852,7 +860,7 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     bf16_t *__restrict__ y, void *__restrict__ state_out, const float *__restrict__ carry,
     const float *__restrict__ tile_decay, const uint4 *__restrict__ frags, const bf16_t *__restrict__ dt_t,
     const float *__restrict__ A_, const SsmTile *__restrict__ tiles, const SsmScanSeq *__restrict__ scan_seqs, int H,
-    int P, int G, int per_stretch, int n_tiles_all)
+    int P, int G, int per_stretch, int n_tiles_all, FixSlots slots, int n_slots)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     FixLds &L = *reinterpret_cast<FixLds *>(lds_raw);
@@ -865,8 +873,16 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     const int slice = b % slices;
     b /= slices;
     const int h = b % H, c = b / H;
-    const SsmScanSeq sq = scan_seqs[scan_seqs[c].of_slot];
-    const int n_tiles = sq.tile_end - sq.tile_begin;
+    int tile_begin, tile_end;
+    if (n_slots <= kFixSlotsInArgs) {
+        tile_begin = slots.tile_begin[c];
+        tile_end = slots.tile_end[c];
+    } else {
+        const SsmScanSeq later = scan_seqs[scan_seqs[c].of_slot];
+        tile_begin = later.tile_begin;
+        tile_end = later.tile_end;
+    }
+    const int n_tiles = tile_end - tile_begin;
     if (j >= n_tiles || j >= per_stretch)
         return;
     const int i = lane & 31, q = lane >> 5;
@@ -878,7 +894,7 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     {
         float part = 0.f;
         for (int k = lane; k < j; k += 64)
-            part += tile_decay[(size_t)h * n_tiles_all + sq.tile_begin + k];
+            part += tile_decay[(size_t)h * n_tiles_all + tile_begin + k];
         cum = read_lane(wave_inclusive_sum(part), 63);
     }
     if (cum < kFixCutoffLog2)
@@ -903,7 +919,7 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     const int yrow = lane >> 3, ycol = 8 * (lane & 7);  // rows of y: 8 lanes x 16 bytes, 8 rows per wave instruction
     const uint32_t lane16 = lane * 16;
     for (int jj = j;;) {
-        const int tile_idx = sq.tile_begin + jj;
+        const int tile_idx = tile_begin + jj;
         const SsmTile t = tiles[tile_idx];
         const rsrc_t img = make_rsrc(reinterpret_cast<const unsigned char *>(frags) +
                                          ((size_t)tile_idx * G + g) * kMfmaTileGroupBytes,
@@ -1033,11 +1049,12 @@ hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const u
 
 template <int ST>
 void launch_fix_st(const ScanArgs &args, const float *carry, const float *tile_decay, const uint4 *frags,
-                   const bf16_t *dt_t, unsigned blocks, int per_stretch, int n_tiles_all, hipStream_t stream)
+                   const bf16_t *dt_t, unsigned blocks, int per_stretch, int n_tiles_all, const FixSlots &slots,
+                   int n_slots, hipStream_t stream)
 {
     hipLaunchKernelGGL(ssm_fix_kernel<ST>, dim3(blocks), dim3(kFixThreads), sizeof(FixLds), stream,
                        static_cast<bf16_t *>(args.y), args.state_out, carry, tile_decay, frags, dt_t, args.A, args.tiles,
-                       args.scan_seqs, args.H, args.P, args.G, per_stretch, n_tiles_all);
+                       args.scan_seqs, args.H, args.P, args.G, per_stretch, n_tiles_all, slots, n_slots);
 }
 
 }  // namespace
@@ -1090,10 +1107,16 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
     const int per_stretch = plan->max_later_tiles < kFixTilesPerStretch ? plan->max_later_tiles : kFixTilesPerStretch;
     const unsigned blocks =
         (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) * (unsigned)((per_stretch + 3) / 4);
+    FixSlots slots = {};
+    for (int c = 0; c < plan->n_carry && c < kFixSlotsInArgs; ++c) {
+        const SsmScanSeq &later = plan->scan_seqs[plan->scan_seqs[c].of_slot];
+        slots.tile_begin[c] = later.tile_begin;
+        slots.tile_end[c] = later.tile_end;
+    }
     switch (args.state_dtype) {
-    case SSM_ST_F16: launch_fix_st<SSM_ST_F16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
-    case SSM_ST_BF16: launch_fix_st<SSM_ST_BF16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
-    default: launch_fix_st<SSM_ST_F32>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, stream); break;
+    case SSM_ST_F16: launch_fix_st<SSM_ST_F16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, slots, plan->n_carry, stream); break;
+    case SSM_ST_BF16: launch_fix_st<SSM_ST_BF16>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, slots, plan->n_carry, stream); break;
+    default: launch_fix_st<SSM_ST_F32>(args, carry, tile_decay, frags, dt_t, blocks, per_stretch, n_tiles, slots, plan->n_carry, stream); break;
     }
     return hipGetLastError();
 }

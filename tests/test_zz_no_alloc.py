@@ -40,6 +40,28 @@ def test_noalloc_entry_matches_ssm_prefill(io):
         assert not torch.isnan(y.float()).any() and not torch.isnan(st[: wl.n_ckpt]).any()
 
 
+def test_noalloc_entry_with_sequences_cut_into_stretches():
+    """A batch small enough for the plan to cut its long sequence into stretches: the stretch table travels through
+    the fixed device array too, and the kernels behind the scan run in the same call."""
+    import paper_2411_19379_amd as ssm
+    shape = LayerShape(8, 64, 128, 2, 256, "bf16")
+    big = make_workload(2, DEV, seed=311, batch=2, len_range=(9000, 13000), shape=shape)
+    small = make_workload(2, DEV, seed=312, batch=1, len_range=(8300, 8300), shape=shape)
+    for wl in (big, small):
+        s = wl.shape
+        plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
+        n_stretches = plan.info.n_stretches
+        plan.close()
+        print(f"noalloc, cut: {wl.seqlens} tokens in {n_stretches} stretches", flush=True)
+        assert n_stretches > wl.batch
+        init = list(wl.init_state)
+        y_ref, st_ref = _run(ssm.ssm_prefill, wl, init)
+        y, st = _run(ssm.ssm_prefill_noalloc, wl, init)
+        assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16))
+        assert torch.equal(st[: wl.n_ckpt].view(torch.int32), st_ref[: wl.n_ckpt].view(torch.int32))
+        assert not torch.isnan(y.float()).any() and not torch.isnan(st[: wl.n_ckpt]).any()
+
+
 def test_noalloc_rejects_oversized_plans():
     import paper_2411_19379_amd as ssm
     # one checkpoint per token makes one tile per token: 17000 tiles > 16384
@@ -51,14 +73,16 @@ def test_noalloc_rejects_oversized_plans():
     plan.close()
 
 
-def test_noalloc_entry_under_graph_capture():
+@pytest.mark.parametrize("lens", [(100, 700), (8200, 9000)])
+def test_noalloc_entry_under_graph_capture(lens):
     """What the entry point is for: a caller that records its work into a HIP graph and may not allocate while it
     does.  The call is captured once (after one eager call, which sets the per-device tables' address up) and
     replayed several times with eager work and synchronisations in between; every replay, on inputs refreshed in
-    place, equals the eager result."""
+    place, equals the eager result.  With the longer requests the plan cuts sequences into stretches, and the kernels
+    that carry the states over are part of the recorded call."""
     import paper_2411_19379_amd as ssm
     shape = LayerShape(8, 64, 128, 2, 256, "bf16")
-    wl = make_workload(2, DEV, seed=303, batch=3, len_range=(100, 700), shape=shape)
+    wl = make_workload(2, DEV, seed=303, batch=3, len_range=lens, shape=shape)
     init = list(wl.init_state)
     s = wl.shape
     plan = ssm.Plan(s.nheads, s.headdim, s.d_state, s.ngroups, s.chunk, s.io_dtype, wl.cu_seqlens, wl.ckpt_pos)
