@@ -791,12 +791,14 @@ constexpr int kFixThreads = 256;
 #ifndef SSM_FIX_TILES_PER_STRETCH
 #define SSM_FIX_TILES_PER_STRETCH 96
 #endif
-constexpr int kFixTilesPerStretch = SSM_FIX_TILES_PER_STRETCH;  // waves per (later stretch, head, 64 channels), a tile each; the last goes on
+constexpr int kFixTilesPerStretch = SSM_FIX_TILES_PER_STRETCH;  // tiles of a later stretch that get a wave of their own; the last one's goes on
+constexpr int kFixTilesPerGroup = 8;     // tiles per workgroup: two per wave
 constexpr float kFixCutoffLog2 = -150.f;
 
 constexpr int LDYT = 64 + 4;  // row stride (floats) of a wave's tile of contributions: 32 tokens x 64 channels
 struct FixLds {
     float ell2[kFixThreads / 64][kQ];
+    uint4 s16[2][4][2][64];  // the carried state of 64 channels as fp16 operands: [channel half][block][k-step][lane]
     float yt[kFixThreads / 64][32][LDYT];
 };
 struct CarryLds {
@@ -852,9 +854,10 @@ __global__ __launch_bounds__(kFixThreads) void ssm_carry_kernel(float *__restric
     }
 }
 
-// One wave per (carry slot, head, 64 channels, tile j < per_stretch of the stretch that starts from the slot), four
-// waves to a workgroup; a wave leaves at once where the decay is below the cutoff.  The wave of the last j goes on
-// tile after tile while the decay is above it.  No workgroup barrier anywhere: waves come and go on their own.
+// One workgroup per (carry slot, head, 64 channels, group of 8 tiles among the first per_stretch tiles of the stretch
+// that starts from the slot).  The workgroup leaves at once if the decay in front of its first tile is below the
+// cutoff; else its four waves convert the carried state to fp16 operands in LDS, a quarter each, and then take two
+// tiles each.  The wave of tile per_stretch - 1 goes on tile after tile while the decay is above the cutoff.
 template <int ST>
 __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     bf16_t *__restrict__ y, void *__restrict__ state_out, const float *__restrict__ carry,
@@ -864,11 +867,11 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     FixLds &L = *reinterpret_cast<FixLds *>(lds_raw);
-    const int slices = P / 64, groups = (per_stretch + 3) / 4;
+    const int slices = P / 64, groups = (per_stretch + kFixTilesPerGroup - 1) / kFixTilesPerGroup;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int b = blockIdx.x;
-    const int j = 4 * (b % groups) + w;
+    const int j0 = kFixTilesPerGroup * (b % groups);
     b /= groups;
     const int slice = b % slices;
     b /= slices;
@@ -883,42 +886,55 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
         tile_end = later.tile_end;
     }
     const int n_tiles = tile_end - tile_begin;
-    if (j >= n_tiles || j >= per_stretch)
+    if (j0 >= n_tiles)
         return;
     const int i = lane & 31, q = lane >> 5;
     const int g = h / (H / G);
     const float Ah = A_[h];
 
-    // decay from the stretch's start to the start of tile j
-    float cum;
+    // Decay from the stretch's start to the start of each of the group's tiles: inclusive sums of the tile decays
+    // 0 .. j0 + 6 (at most 102 of them: two per lane), every wave for itself.
+    float incl0, incl1;
     {
-        float part = 0.f;
-        for (int k = lane; k < j; k += 64)
-            part += tile_decay[(size_t)h * n_tiles_all + tile_begin + k];
-        cum = read_lane(wave_inclusive_sum(part), 63);
+        const float *d = tile_decay + (size_t)h * n_tiles_all + tile_begin;
+        const int need = j0 + kFixTilesPerGroup - 1 < n_tiles ? j0 + kFixTilesPerGroup - 1 : n_tiles;
+        incl0 = wave_inclusive_sum(lane < need ? d[lane] : 0.f);
+        incl1 = wave_inclusive_sum(64 + lane < need ? d[64 + lane] : 0.f) + read_lane(incl0, 63);
     }
-    if (cum < kFixCutoffLog2)
-        return;
+    auto decay_before = [&](int j) {  // j is uniform in the wave
+        return j == 0 ? 0.f : j <= 64 ? read_lane(incl0, j - 1) : read_lane(incl1, j - 65);
+    };
+    if (decay_before(j0) < kFixCutoffLog2)
+        return;  // the whole workgroup: every wave computes the same value
 
     // the carried state of the 64 channels as fp16 operands, in the order the scan uses for S.C; the slot holds the
     // register image the scan left: [head][block of 32 channels][block of 32 state indices][a][lane] float4
     const size_t state_row = ((size_t)h * P + 64 * slice + i) * kN + 4 * q;  // + 32 cc kN: channel half cc
     const float4 *S = reinterpret_cast<const float4 *>(carry + (size_t)c * H * P * kN) +
                       ((size_t)h * (P / 32) + 2 * slice) * (16 * 64) + lane;
-    uint4 s16[2][4][2];
+    {
+        const int cc = w >> 1;
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+        for (int n2 = 0; n2 < 2; ++n2)
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
+                const int nb = 2 * (w & 1) + n2;
                 const float4 lo = S[((cc * 4 + nb) * 4 + 2 * hf) * 64], hi = S[((cc * 4 + nb) * 4 + 2 * hf + 1) * 64];
-                s16[cc][nb][hf] = make_uint4(pack2_f16(lo.x, lo.y), pack2_f16(lo.z, lo.w), pack2_f16(hi.x, hi.y),
-                                             pack2_f16(hi.z, hi.w));
+                L.s16[cc][nb][hf][lane] = make_uint4(pack2_f16(lo.x, lo.y), pack2_f16(lo.z, lo.w),
+                                                     pack2_f16(hi.x, hi.y), pack2_f16(hi.z, hi.w));
             }
+    }
+    lds_barrier();  // the only one; after it the waves go their own ways
     const int yrow = lane >> 3, ycol = 8 * (lane & 7);  // rows of y: 8 lanes x 16 bytes, 8 rows per wave instruction
     const uint32_t lane16 = lane * 16;
-    for (int jj = j;;) {
+    for (int r = 0; r < kFixTilesPerGroup / 4; ++r) {
+      const int j = j0 + 4 * r + w;
+      if (j >= n_tiles || j >= per_stretch)
+          break;
+      float cum = decay_before(j);
+      if (cum < kFixCutoffLog2)
+          break;
+      for (int jj = j;;) {
         const int tile_idx = tile_begin + jj;
         const SsmTile t = tiles[tile_idx];
         const rsrc_t img = make_rsrc(reinterpret_cast<const unsigned char *>(frags) +
@@ -944,7 +960,7 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
                 f32x16 acc = zero16();
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    acc = mfma_f16(s16[cc][ks >> 1][ks & 1], cfr[ks], acc);
+                    acc = mfma_f16(L.s16[cc][ks >> 1][ks & 1][lane], cfr[ks], acc);
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
                     *reinterpret_cast<float4 *>(&L.yt[w][i][32 * cc + 8 * a + 4 * q]) =
@@ -1004,6 +1020,7 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
         }
         if (j != per_stretch - 1 || ++jj >= n_tiles || cum < kFixCutoffLog2)
             break;
+      }
     }
 }
 
@@ -1105,8 +1122,8 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
             return e;
     }
     const int per_stretch = plan->max_later_tiles < kFixTilesPerStretch ? plan->max_later_tiles : kFixTilesPerStretch;
-    const unsigned blocks =
-        (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) * (unsigned)((per_stretch + 3) / 4);
+    const unsigned blocks = (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) *
+                            (unsigned)((per_stretch + kFixTilesPerGroup - 1) / kFixTilesPerGroup);
     FixSlots slots = {};
     for (int c = 0; c < plan->n_carry && c < kFixSlotsInArgs; ++c) {
         const SsmScanSeq &later = plan->scan_seqs[plan->scan_seqs[c].of_slot];

@@ -27,8 +27,8 @@ static bool filter(int launch, unsigned b)
     }
     if (launch < g_launches_before_fix)  // completing the carried states: block = slot * H + head
         return has_head(b % gH);
-    // adding the carried states' contribution: block = ((slot * H + head) * slices + slice) * groups of 4 tiles + group
-    return has_head((b / ((g_fix_per_stretch + 3) / 4) / (gP / 64)) % gH);
+    // adding the carried states' contribution: block = ((slot * H + head) * slices + slice) * groups of 8 tiles + group
+    return has_head((b / ((g_fix_per_stretch + 7) / 8) / (gP / 64)) % gH);
 }
 static uint32_t hash32(uint64_t x) { x ^= x >> 33; x *= 0xff51afd7ed558ccdULL; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ULL; x ^= x >> 33; return (uint32_t)x; }
 static float unif(uint64_t k) { return (hash32(k) >> 8) * (1.0f / 16777216.0f); }
