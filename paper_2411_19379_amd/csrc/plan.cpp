@@ -169,21 +169,22 @@ extern "C" int ssm_plan_create(const ssm_shape_t *shape, int32_t batch,
     }
     plan->n_workgroups = (int32_t)wgs;
     if (plan->path == SSM_PATH_MFMA_BF16)
-        ssm_plan_build_stretches(plan, kMfmaWideMinWorkgroups, kMfmaMinStretchTiles);
+        ssm_plan_build_stretches(plan, kMfmaWorkgroupsPerRound, kMfmaMinStretchTiles);
     *out = plan;
     return SSM_OK;
 }
 
 static void ssm_plan_order_sequences(ssm_plan *plan);
 
-void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_tiles)
+void ssm_plan_build_stretches(ssm_plan *plan, int64_t per_round, int32_t min_tiles)
 {
     const ssm_shape_t &s = plan->shape;
     const int32_t batch = plan->batch;
     auto seq_tiles = [&](int32_t i) { return plan->seqs[i].tile_end - plan->seqs[i].tile_begin; };
     // A batch with too few (sequence, head, 64-channel slice) streams to occupy the GPU has its long sequences cut
-    // into stretches.  The scan has a variant whose workgroups own 64 channels of a head instead of 32: one set of
-    // operand loads serves twice the rows, at half the number of workgroups; it runs if those still fill the GPU.
+    // into stretches, as many as still run in one round.  The scan has a variant whose workgroups own 64 channels of
+    // a head instead of 32: one set of operand loads serves twice the rows, at half the number of workgroups; it
+    // runs where the 32-channel variant would need a second round.
     std::vector<int32_t> parts(batch, 1);
     plan->p_split = s.headdim / 32;
     if (s.headdim % kMfmaWideChannels == 0) {
@@ -192,8 +193,8 @@ void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_
         for (int32_t i = 0; i < batch; ++i)
             active += seq_tiles(i) > 0;
         int64_t stretches = active;
-        if (active > 0 && active * per_seq < want_streams && min_tiles > 0) {
-            const int64_t k_want = (want_streams + active * per_seq - 1) / (active * per_seq);
+        const int64_t k_want = active > 0 ? per_round / (active * per_seq) : 0;
+        if (k_want >= 2 && min_tiles > 0) {
             stretches = 0;
             for (int32_t i = 0; i < batch; ++i)
                 if (seq_tiles(i) > 0) {
@@ -201,7 +202,7 @@ void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_
                     stretches += parts[i];
                 }
         }
-        if (stretches * per_seq >= want_streams)
+        if (2 * stretches * per_seq > per_round)
             plan->p_split = s.headdim / kMfmaWideChannels;
     }
     plan->scan_seqs.clear();

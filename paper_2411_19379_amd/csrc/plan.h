@@ -111,9 +111,10 @@ struct ssm_plan {
 void ssm_set_error(const std::string &msg);
 
 // Matrix-core scan: (re)builds the stretches, p_split, the carry slots, the launch order and n_workgroups from the
-// tiles and the shape.  When the batch has fewer than `want_streams` (sequence, head, 64-channel slice) streams, long
-// sequences are cut into stretches of at least `min_tiles` tiles, as many as it takes to reach that number.
-void ssm_plan_build_stretches(ssm_plan *plan, int64_t want_streams, int32_t min_tiles);
+// tiles and the shape.  `per_round` workgroups run at a time.  With s (sequence, head, 64-channel slice) streams, long
+// sequences are cut into floor(per_round / s) stretches of at least `min_tiles` tiles each; the 64-channel variant is
+// chosen if the 32-channel one would not fit one round.
+void ssm_plan_build_stretches(ssm_plan *plan, int64_t per_round, int32_t min_tiles);
 
 // Where the parts of the matrix-core scan's workspace start (bytes from its base), and its size.
 struct SsmMfmaWorkspace {
@@ -134,10 +135,12 @@ constexpr int kMfmaTileTokens = 64;
 constexpr size_t kMfmaTileGroupBytes = 38912;
 constexpr size_t kMfmaDtBytes = 128;
 
-// The wide variant of the matrix-core scan (64 channels of a head per workgroup instead of 32) is chosen when it
-// still has at least this many workgroups with work: one per compute unit of the GPU this library is written for.
+// The GPU this library is written for takes one workgroup of the matrix-core scan per compute unit, 256 at a time.
+// The wide variant of the scan (64 channels of a head per workgroup instead of 32) is chosen when the narrow one would
+// need more workgroups than that, i.e. a second round; long sequences are cut into as many stretches as still fit
+// one round of the wide variant.
 constexpr int kMfmaWideChannels = 64;
-constexpr int kMfmaWideMinWorkgroups = 256;
+constexpr int kMfmaWorkgroupsPerRound = 256;
 
 // A sequence is cut into stretches only if each gets at least this many tiles (the second kernel's work per stretch
 // does not shrink with the stretch).

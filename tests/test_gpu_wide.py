@@ -1,5 +1,5 @@
 """GPU parity of the variant of the matrix-core scan whose workgroups own 64 channels of a head.  The plan picks it
-when at least 256 (sequence, head, 64-channel slice) streams have work, so these batches are small in tokens but
+when more than 128 (sequence, head, 64-channel slice) streams have work, so these batches are small in tokens but
 wide in heads; every head is compared with the oracle."""
 import numpy as np
 import pytest
@@ -29,8 +29,10 @@ def _with_empty_sequence(wl):
     ("p64", LayerShape(64, 64, 128, 4, 256, "bf16"), 4, 4 * 64),
     # headdim 128: two 64-channel slices per head
     ("p128", LayerShape(32, 128, 128, 2, 256, "bf16"), 4, 4 * 32 * 2),
-    # one stream short of the threshold: the 32-channel kernel serves the same kind of batch
-    ("p64_narrow", LayerShape(51, 64, 128, 1, 256, "bf16"), 5, 5 * 51 * 2),
+    # 255 streams: the 32-channel kernel would need a second round of workgroups, so still the 64-channel one
+    ("p64_255", LayerShape(51, 64, 128, 1, 256, "bf16"), 5, 5 * 51),
+    # 125 streams: the 32-channel kernel's 250 workgroups fit one round
+    ("p64_narrow", LayerShape(25, 64, 128, 1, 256, "bf16"), 5, 5 * 25 * 2),
 ])
 def test_wide_and_narrow_kernels_match_the_oracle(case, shape, batch, want_wgs):
     say(f"{case}: H={shape.nheads} P={shape.headdim}, {batch} requests of 1..400 tokens, half of them cache hits, "

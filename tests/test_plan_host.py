@@ -89,9 +89,9 @@ def test_random_batches_are_covered(io, shape, path, tile):
         assert ssm.ssm_plan_workspace_bytes(plan.handle) == (want_ws + 255) // 256 * 256
         split = 1
         if path == ssm.SSM_PATH_MFMA_BF16:
-            # 32 channels of a head per workgroup, or 64 as soon as that still leaves 256 workgroups with work
+            # 32 channels of a head per workgroup, or 64 where that would take more than the 256 workgroups of a round
             busy = sum(1 for L in lens if L > 0)
-            split = P // 64 if P % 64 == 0 and busy * H * (P // 64) >= 256 else P // 32
+            split = P // 64 if P % 64 == 0 and 2 * busy * H * (P // 64) > 256 else P // 32
         assert plan.info.n_workgroups == nb * H * split
         plan.close()
 
@@ -196,8 +196,9 @@ def test_launch_order_covers_every_item_once_and_balances_the_dies():
 
 
 def test_long_sequences_of_small_batches_are_cut_into_stretches():
-    """A batch with fewer than 256 (sequence, head, 64-channel slice) streams: its long sequences are cut into
-    stretches of at least 64 tiles until there are 256, the stretches of a sequence partition its tiles in order, only
+    """A batch with at most 128 (sequence, head, 64-channel slice) streams: its long sequences are cut into
+    stretches of at least 64 tiles, as many as fit one round of 256 workgroups, the stretches of a sequence partition
+    its tiles in order, only
     the first does not start from zero, and the workspace has room for one fp32 state per later stretch and one fp32
     per (tile, head).  Batches that fill the GPU, short sequences and the fp32 path are left alone."""
     def plan_of(lens, H=128, P=64, io="bf16", ckpt=None):
@@ -239,9 +240,12 @@ def test_long_sequences_of_small_batches_are_cut_into_stretches():
     p = plan_of([2048], H=80)   # too short to cut
     assert p.info.n_stretches == 1 and p.info.n_workgroups == 160
     p.close()
-    p = plan_of([20000, 300, 0, 9000], H=40)  # 120 streams: cut in three where long enough, else two, else not
-    assert [e - b for b, e, _ in p.stretches()] == [104, 104, 105, 5, 0, 70, 71]
-    assert check_partition(p, [20000, 300, 0, 9000]) == 3
+    p = plan_of([20000, 300, 0, 9000], H=40)  # 120 streams: two stretches where long enough; 200 streams, 64 channels
+    assert [e - b for b, e, _ in p.stretches()] == [156, 157, 5, 0, 70, 71]
+    assert check_partition(p, [20000, 300, 0, 9000]) == 2 and p.info.n_workgroups == 6 * 40
+    p.close()
+    p = plan_of([20000, 20000], H=80)  # 160 streams: a second round either way with 32 channels; 64 channels, uncut
+    assert p.info.n_stretches == 2 and p.info.n_workgroups == 160
     p.close()
     p = plan_of([16384, 16384])  # 256 streams: nothing to cut
     assert p.info.n_stretches == 2 and not any(z for _, _, z in p.stretches())
