@@ -103,6 +103,81 @@ def cpu_baseline(wl, sample_tokens: int, min_seconds: float = 10.0, max_repeats:
                       f"one checkpoint, {reps} passes; {el:.1f} s"}
 
 
+def side_op(args, ssm, torch, dev) -> int:
+    """The kernels beside the scan at the 7B layer shape, each HBM-streaming: the decode step over a batch of cached
+    states (`ssm_state_advance`, one token per sequence: every state is read and written once) and the causal
+    convolution in front of the scan over 32768 tokens (`ssm_conv1d_prefill`: input read once, output written once).
+    One JSON line with the achieved fraction of the HBM roofline on the algorithmic bytes."""
+    from workloads import LayerShape
+    from workloads.gen import _gen, draw_layer_inputs, draw_layer_params
+
+    shape = LayerShape(128, 64, 128, 8, 256, "bf16")
+    H, P, N, G = shape.nheads, shape.headdim, shape.d_state, shape.ngroups
+    g = _gen(dev, 77)
+    stream = torch.cuda.current_stream().cuda_stream
+    if args.op == "advance":
+        batch = args.decode_batch
+        A, D = draw_layer_params(shape, g, dev)
+        inp = draw_layer_inputs(shape, batch, g, dev)
+        states = [torch.randn((H, P, N), generator=g, device=dev) for _ in range(batch)]
+        plan = ssm.Plan(H, P, N, G, shape.chunk, "bf16", list(range(batch + 1)), [[] for _ in range(batch)])
+        y = torch.empty_like(inp.x)
+        ptrs = [t.data_ptr() for t in states]
+
+        def step():
+            ssm.ssm_state_advance(plan.handle, inp.x.data_ptr(), inp.dt.data_ptr(), A.data_ptr(), inp.B.data_ptr(),
+                                  inp.C.data_ptr(), D.data_ptr(), ptrs, y.data_ptr(), stream)
+
+        tokens = batch
+        abytes = batch * (2 * H * P * N * 4 + (2 * H * P + H + 2 * G * N) * 2)
+        name, kernel, metric = f"advance_7b_decode_b{batch}", "ssm_advance_kernel", "decode-step tokens/s per SSM layer (1 GPU)"
+    else:
+        T, K = 32768, 4
+        C = H * P + 2 * G * N
+        xin = torch.randn((T, C), generator=g, device=dev).to(torch.bfloat16)
+        w = (torch.randn((C, K), generator=g, device=dev) / K ** 0.5).float()
+        bias = torch.randn((C,), generator=g, device=dev).float()
+        plan = ssm.Plan(H, P, N, G, shape.chunk, "bf16", [0, T], [[T]])
+        out = torch.empty_like(xin)
+        st = torch.empty((1, C, K), dtype=torch.bfloat16, device=dev)
+
+        def step():
+            ssm.ssm_conv1d_prefill(plan.handle, C, K, xin.data_ptr(), w.data_ptr(), bias.data_ptr(), None,
+                                   out.data_ptr(), st.data_ptr(), 1, stream)
+
+        tokens = T
+        abytes = 2 * T * C * 2 + C * K * 2
+        name, kernel, metric = "conv1d_7b_32k_k4", "ssm_conv1d_kernel", "convolution tokens/s per SSM layer (1 GPU)"
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev = []
+    for _ in range(args.steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        step()
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    plan.close()
+    achieved = abytes / (kern_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": metric, "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "tokens": tokens, "nheads": H, "headdim": P, "d_state": N, "ngroups": G},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernel, "kernel_ms": kern_ms,
+                     "algorithmic_bytes": abytes}}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +188,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--decode-batch", type=int, default=64, help="sequences of --op advance (one token each)")
+    ap.add_argument("--op", choices=["prefill", "advance", "conv1d"], default="prefill",
+                    help="prefill: the hot path (default); advance / conv1d: the two kernels beside it, one line each")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -129,6 +207,8 @@ def main() -> int:
         return 2
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.op != "prefill":
+        return side_op(args, ssm, torch, dev)
     wl = make_workload(args.config, dev)
     s = wl.shape
     inp = wl.inputs

@@ -256,7 +256,8 @@ int ssm_state_advance(const ssm_plan_t *plan,
  * (zeros without one); weight[c,K-1] multiplies the current token; activation
  * 0 is the identity, 1 is SiLU.
  *
- *   in, out    [T,channels]   io_dtype of the plan, device
+ *   in, out    [T,channels]   io_dtype of the plan, device; two buffers that do
+ *                             not overlap
  *   weight     [channels,K]   fp32, device;  bias [channels] fp32 or NULL
  *   init_state_ptrs           NULL, or HOST array [batch] of DEVICE pointers
  *                             (NULL entry: zeros) to [channels,K] in io_dtype:

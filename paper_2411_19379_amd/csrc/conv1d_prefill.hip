@@ -81,8 +81,8 @@ __global__ __launch_bounds__(kConvThreads) void ssm_conv1d_kernel(ConvArgs a)
     const int seq_tok0 = a.tiles[a.seqs[t.seq].tile_begin].tok0;
     const int lp = t.tok0 - seq_tok0;  // tokens of this sequence in front of the tile
 
-    const IO *in = static_cast<const IO *>(a.in);
-    IO *out = static_cast<IO *>(a.out);
+    const IO *__restrict__ in = static_cast<const IO *>(a.in);  // the caller keeps in and out apart
+    IO *__restrict__ out = static_cast<IO *>(a.out);
     const IO *init = a.init_ptrs ? static_cast<const IO *>(a.init_ptrs[t.seq]) : nullptr;
 
     float wk[K][V], bias[V];
@@ -116,10 +116,25 @@ __global__ __launch_bounds__(kConvThreads) void ssm_conv1d_kernel(ConvArgs a)
         }
     }
 
-    for (int i = 0; i < t.len; ++i) {
-        const size_t tok = (size_t)t.tok0 + i;
+    // Groups of kAhead tokens: the group's rows are requested together, then consumed in order, so that a thread has
+    // several loads in flight instead of one per trip.
+    constexpr int kAhead = 8;
+    for (int i0 = 0; i0 < t.len; i0 += kAhead) {
+      float row[kAhead][V];
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) {
+          const int i = i0 + u < t.len ? i0 + u : t.len - 1;  // past the end: the last row again, unused
+          ConvVec<IO>::load(in + ((size_t)t.tok0 + i) * Cch + c0, row[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) {
+        if (i0 + u >= t.len)
+            break;
+        const size_t tok = (size_t)t.tok0 + i0 + u;
         float cur[V], v[V];
-        ConvVec<IO>::load(in + tok * Cch + c0, cur);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+            cur[e] = row[u][e];
 #pragma unroll
         for (int e = 0; e < V; ++e) {
             float acc = bias[e];
@@ -141,6 +156,7 @@ __global__ __launch_bounds__(kConvThreads) void ssm_conv1d_kernel(ConvArgs a)
 #pragma unroll
         for (int e = 0; e < V; ++e)
             hist[0][e] = cur[e];
+      }
     }
 
     if (t.ckpt_slot >= 0) {
