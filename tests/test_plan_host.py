@@ -253,3 +253,22 @@ def test_long_sequences_of_small_batches_are_cut_into_stretches():
     p = plan_of([32768], H=8, io="f32")
     assert p.info.n_stretches == 1
     p.close()
+
+
+def test_stretch_queries_reject_bad_indices_and_cover_the_fp32_path():
+    p = ssm.Plan(4, 16, 16, 1, 64, "f32", [0, 100, 100, 300], None)  # vector-ALU path: one stretch per sequence
+    assert p.info.n_stretches == 3
+    tiles = p.tiles()
+    st = p.stretches()
+    assert [z for _, _, z in st] == [False, False, False]
+    for i, (b, e, _) in enumerate(st):
+        assert all(t[2] == i for t in tiles[b:e]) and e - b == sum(1 for t in tiles if t[2] == i)
+    for bad in (-1, 3):
+        with pytest.raises(ssm.SsmError) as err:
+            ssm.ssm_plan_stretch(p.handle, bad)
+        assert err.value.status == "SSM_ERR_INVALID_ARG"
+    p.close()
+    q = ssm.Plan(128, 64, 128, 8, 256, "bf16", [0, 32768], None)
+    with pytest.raises(ssm.SsmError):
+        ssm.ssm_plan_stretch(q.handle, 2)
+    q.close()
