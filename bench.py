@@ -193,7 +193,7 @@ def main() -> int:
                     help="prefill: the hot path (default); advance / conv1d: the two kernels beside it, one line each")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1", file=sys.stderr)
         return 2
 
     import torch
