@@ -198,7 +198,10 @@ void ssm_plan_build_stretches(ssm_plan *plan, int64_t per_round, int32_t min_til
             stretches = 0;
             for (int32_t i = 0; i < batch; ++i)
                 if (seq_tiles(i) > 0) {
-                    parts[i] = (int32_t)std::max<int64_t>(1, std::min<int64_t>(k_want, seq_tiles(i) / min_tiles));
+                    // kMfmaMinCutTiles belongs to the default min_tiles; a caller that passes a smaller one means it
+                    const int64_t min_cut = min_tiles >= kMfmaMinStretchTiles ? kMfmaMinCutTiles : 2 * (int64_t)min_tiles;
+                    if (seq_tiles(i) >= min_cut)
+                        parts[i] = (int32_t)std::max<int64_t>(1, std::min<int64_t>(k_want, seq_tiles(i) / min_tiles));
                     stretches += parts[i];
                 }
         }

@@ -197,7 +197,7 @@ def test_launch_order_covers_every_item_once_and_balances_the_dies():
 
 def test_long_sequences_of_small_batches_are_cut_into_stretches():
     """A batch with at most 128 (sequence, head, 64-channel slice) streams: its long sequences are cut into
-    stretches of at least 64 tiles, as many as fit one round of 256 workgroups, the stretches of a sequence partition
+    stretches of at least 64 tiles (sequences of at least 160 tiles), as many as fit one round of 256 workgroups, the stretches of a sequence partition
     its tiles in order, only
     the first does not start from zero, and the workspace has room for one fp32 state per later stretch and one fp32
     per (tile, head).  Batches that fill the GPU, short sequences and the fp32 path are left alone."""
@@ -240,9 +240,12 @@ def test_long_sequences_of_small_batches_are_cut_into_stretches():
     p = plan_of([2048], H=80)   # too short to cut
     assert p.info.n_stretches == 1 and p.info.n_workgroups == 160
     p.close()
-    p = plan_of([20000, 300, 0, 9000], H=40)  # 120 streams: two stretches where long enough; 200 streams, 64 channels
-    assert [e - b for b, e, _ in p.stretches()] == [156, 157, 5, 0, 70, 71]
-    assert check_partition(p, [20000, 300, 0, 9000]) == 2 and p.info.n_workgroups == 6 * 40
+    p = plan_of([20000, 300, 0, 9000 + 1300], H=40)  # 120 streams: two stretches where long enough; 200 streams, 64 channels
+    assert [e - b for b, e, _ in p.stretches()] == [156, 157, 5, 0, 80, 81]
+    assert check_partition(p, [20000, 300, 0, 10300]) == 2 and p.info.n_workgroups == 6 * 40
+    p.close()
+    p = plan_of([10240 - 64, 10240], H=40)  # 159 and 160 tiles: only the second is long enough to be cut
+    assert [e - b for b, e, _ in p.stretches()] == [159, 80, 80]
     p.close()
     p = plan_of([20000, 20000], H=80)  # 160 streams: a second round either way with 32 channels; 64 channels, uncut
     assert p.info.n_stretches == 2 and p.info.n_workgroups == 160
