@@ -788,11 +788,21 @@ __global__ __launch_bounds__(64 * NW) void ssm_scan_mfma_kernel(
 // stretch).  The decay only shrinks along the stretch: once it is below 2^-150 nothing is added in fp32 and the rest
 // of the stretch is left alone, which for decay rates as trained models have them is all but its first few tiles.
 constexpr int kFixThreads = 256;
-#ifndef SSM_FIX_TILES_PER_STRETCH
-#define SSM_FIX_TILES_PER_STRETCH 96
+// A stretch's first kFixFineTiles tiles, where the carried state usually still counts, go to workgroups of 8 tiles
+// (two per wave); the rest, which it reaches only when decay is unusually slow, to workgroups of 32 (eight per wave).
+#ifndef SSM_FIX_FINE_TILES
+#define SSM_FIX_FINE_TILES 96
 #endif
-constexpr int kFixTilesPerStretch = SSM_FIX_TILES_PER_STRETCH;  // tiles of a later stretch that get a wave of their own; the last one's goes on
-constexpr int kFixTilesPerGroup = 8;     // tiles per workgroup: two per wave
+constexpr int kFixFineTiles = SSM_FIX_FINE_TILES;
+constexpr int kFixFineGroup = 8, kFixCoarseGroup = 32;
+static_assert(kFixFineTiles % kFixFineGroup == 0, "whole groups");
+// workgroups per (carry slot, head, 64 channels) for stretches of up to `tiles` tiles
+__host__ __device__ inline int fix_groups(int tiles)
+{
+    if (tiles <= kFixFineTiles)
+        return (tiles + kFixFineGroup - 1) / kFixFineGroup;
+    return kFixFineTiles / kFixFineGroup + (tiles - kFixFineTiles + kFixCoarseGroup - 1) / kFixCoarseGroup;
+}
 constexpr float kFixCutoffLog2 = -150.f;
 
 constexpr int LDYT = 64 + 4;  // row stride (floats) of a wave's tile of contributions: 32 tokens x 64 channels
@@ -854,24 +864,26 @@ __global__ __launch_bounds__(kFixThreads) void ssm_carry_kernel(float *__restric
     }
 }
 
-// One workgroup per (carry slot, head, 64 channels, group of 8 tiles among the first per_stretch tiles of the stretch
-// that starts from the slot).  The workgroup leaves at once if the decay in front of its first tile is below the
-// cutoff; else its four waves convert the carried state to fp16 operands in LDS, a quarter each, and then take two
-// tiles each.  The wave of tile per_stretch - 1 goes on tile after tile while the decay is above the cutoff.
+// One workgroup per (carry slot, head, 64 channels, group of tiles of the stretch that starts from the slot).  The
+// workgroup leaves at once if the decay in front of its first tile is below the cutoff; else its four waves convert
+// the carried state to fp16 operands in LDS, a quarter each, and then take every fourth tile of the group each.
 template <int ST>
 __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     bf16_t *__restrict__ y, void *__restrict__ state_out, const float *__restrict__ carry,
     const float *__restrict__ tile_decay, const uint4 *__restrict__ frags, const bf16_t *__restrict__ dt_t,
     const float *__restrict__ A_, const SsmTile *__restrict__ tiles, const SsmScanSeq *__restrict__ scan_seqs, int H,
-    int P, int G, int per_stretch, int n_tiles_all, FixSlots slots, int n_slots)
+    int P, int G, int max_tiles, int n_tiles_all, FixSlots slots, int n_slots)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     FixLds &L = *reinterpret_cast<FixLds *>(lds_raw);
-    const int slices = P / 64, groups = (per_stretch + kFixTilesPerGroup - 1) / kFixTilesPerGroup;
+    const int slices = P / 64, groups = fix_groups(max_tiles);
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int b = blockIdx.x;
-    const int j0 = kFixTilesPerGroup * (b % groups);
+    const int grp = b % groups;
+    const bool fine = grp < kFixFineTiles / kFixFineGroup;
+    const int j0 = fine ? kFixFineGroup * grp : kFixFineTiles + kFixCoarseGroup * (grp - kFixFineTiles / kFixFineGroup);
+    const int group_tiles = fine ? kFixFineGroup : kFixCoarseGroup;
     b /= groups;
     const int slice = b % slices;
     b /= slices;
@@ -892,19 +904,21 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     const int g = h / (H / G);
     const float Ah = A_[h];
 
-    // Decay from the stretch's start to the start of each of the group's tiles: inclusive sums of the tile decays
-    // 0 .. j0 + 6 (at most 102 of them: two per lane), every wave for itself.
-    float incl0, incl1;
+    // Decay from the stretch's start to the start of each of the group's tiles: the sum of the tile decays in front
+    // of the group (contiguous wave loads) plus the inclusive sums inside it (at most 32), every wave for itself.
+    float before_group, incl;
     {
         const float *d = tile_decay + (size_t)h * n_tiles_all + tile_begin;
-        const int need = j0 + kFixTilesPerGroup - 1 < n_tiles ? j0 + kFixTilesPerGroup - 1 : n_tiles;
-        incl0 = wave_inclusive_sum(lane < need ? d[lane] : 0.f);
-        incl1 = wave_inclusive_sum(64 + lane < need ? d[64 + lane] : 0.f) + read_lane(incl0, 63);
+        float part = 0.f;
+        for (int k = lane; k < j0; k += 64)
+            part += d[k];
+        before_group = read_lane(wave_inclusive_sum(part), 63);
+        incl = wave_inclusive_sum(lane < group_tiles && j0 + lane < n_tiles ? d[j0 + lane] : 0.f);
     }
-    auto decay_before = [&](int j) {  // j is uniform in the wave
-        return j == 0 ? 0.f : j <= 64 ? read_lane(incl0, j - 1) : read_lane(incl1, j - 65);
+    auto decay_before = [&](int j) {  // j is uniform in the wave, j0 <= j < j0 + group_tiles
+        return j == j0 ? before_group : before_group + read_lane(incl, j - j0 - 1);
     };
-    if (decay_before(j0) < kFixCutoffLog2)
+    if (before_group < kFixCutoffLog2)
         return;  // the whole workgroup: every wave computes the same value
 
     // the carried state of the 64 channels as fp16 operands, in the order the scan uses for S.C; the slot holds the
@@ -927,15 +941,15 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
     lds_barrier();  // the only one; after it the waves go their own ways
     const int yrow = lane >> 3, ycol = 8 * (lane & 7);  // rows of y: 8 lanes x 16 bytes, 8 rows per wave instruction
     const uint32_t lane16 = lane * 16;
-    for (int r = 0; r < kFixTilesPerGroup / 4; ++r) {
+    for (int r = 0; r < group_tiles / 4; ++r) {
       const int j = j0 + 4 * r + w;
-      if (j >= n_tiles || j >= per_stretch)
+      if (j >= n_tiles)
           break;
       float cum = decay_before(j);
       if (cum < kFixCutoffLog2)
           break;
-      for (int jj = j;;) {
-        const int tile_idx = tile_begin + jj;
+      {
+        const int tile_idx = tile_begin + j;
         const SsmTile t = tiles[tile_idx];
         const rsrc_t img = make_rsrc(reinterpret_cast<const unsigned char *>(frags) +
                                          ((size_t)tile_idx * G + g) * kMfmaTileGroupBytes,
@@ -1018,8 +1032,6 @@ __global__ __launch_bounds__(kFixThreads) void ssm_fix_kernel(
                         store_state4(state_out, slot + idx, v, ST);
                     }
         }
-        if (j != per_stretch - 1 || ++jj >= n_tiles || cum < kFixCutoffLog2)
-            break;
       }
     }
 }
@@ -1066,12 +1078,12 @@ hipError_t launch_scan_width(const ssm_plan *plan, const ScanArgs &args, const u
 
 template <int ST>
 void launch_fix_st(const ScanArgs &args, const float *carry, const float *tile_decay, const uint4 *frags,
-                   const bf16_t *dt_t, unsigned blocks, int per_stretch, int n_tiles_all, const FixSlots &slots,
+                   const bf16_t *dt_t, unsigned blocks, int max_tiles, int n_tiles_all, const FixSlots &slots,
                    int n_slots, hipStream_t stream)
 {
     hipLaunchKernelGGL(ssm_fix_kernel<ST>, dim3(blocks), dim3(kFixThreads), sizeof(FixLds), stream,
                        static_cast<bf16_t *>(args.y), args.state_out, carry, tile_decay, frags, dt_t, args.A, args.tiles,
-                       args.scan_seqs, args.H, args.P, args.G, per_stretch, n_tiles_all, slots, n_slots);
+                       args.scan_seqs, args.H, args.P, args.G, max_tiles, n_tiles_all, slots, n_slots);
 }
 
 }  // namespace
@@ -1121,9 +1133,9 @@ hipError_t launch_scan_mfma(const ssm_plan *plan, const ScanArgs &args, void *wo
         if ((e = hipGetLastError()) != hipSuccess)
             return e;
     }
-    const int per_stretch = plan->max_later_tiles < kFixTilesPerStretch ? plan->max_later_tiles : kFixTilesPerStretch;
-    const unsigned blocks = (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) *
-                            (unsigned)((per_stretch + kFixTilesPerGroup - 1) / kFixTilesPerGroup);
+    const int per_stretch = plan->max_later_tiles;
+    const unsigned blocks =
+        (unsigned)plan->n_carry * (unsigned)args.H * (unsigned)(args.P / 64) * (unsigned)fix_groups(per_stretch);
     FixSlots slots = {};
     for (int c = 0; c < plan->n_carry && c < kFixSlotsInArgs; ++c) {
         const SsmScanSeq &later = plan->scan_seqs[plan->scan_seqs[c].of_slot];

@@ -11,7 +11,7 @@
 #include "emu_host.h"
 namespace emu { void set_order_mode(int m); void set_block_filter(bool (*)(int, unsigned)); long switches(); }
 
-static int gH, gP, gG, g_psplit, g_items, g_prep_parts = 1, g_fix_per_stretch = 1, g_launches_before_fix = 2;
+static int gH, gP, gG, g_psplit, g_items, g_prep_parts = 1, g_fix_groups = 1, g_launches_before_fix = 2;
 static std::vector<int> g_heads;  // heads whose workgroups run
 static bool has_head(int h) { for (int x : g_heads) if (x == h) return true; return false; }
 static bool filter(int launch, unsigned b)
@@ -27,8 +27,8 @@ static bool filter(int launch, unsigned b)
     }
     if (launch < g_launches_before_fix)  // completing the carried states: block = slot * H + head
         return has_head(b % gH);
-    // adding the carried states' contribution: block = ((slot * H + head) * slices + slice) * groups of 8 tiles + group
-    return has_head((b / ((g_fix_per_stretch + 7) / 8) / (gP / 64)) % gH);
+    // adding the carried states' contribution: block = ((slot * H + head) * slices + slice) * groups + group
+    return has_head((b / g_fix_groups / (gP / 64)) % gH);
 }
 static uint32_t hash32(uint64_t x) { x ^= x >> 33; x *= 0xff51afd7ed558ccdULL; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ULL; x ^= x >> 33; return (uint32_t)x; }
 static float unif(uint64_t k) { return (hash32(k) >> 8) * (1.0f / 16777216.0f); }
@@ -44,7 +44,11 @@ int main(int argc, char **argv)
     ssm_plan_t *plan; if (ssm_plan_create(&sh, 1, cu, cuck, ck.data(), &plan)) { printf("plan: %s\n", ssm_last_error()); return 1; }
     g_psplit = plan->p_split; g_items = plan->n_items;
     g_prep_parts = (long long)plan->tiles.size() * G < kMfmaPrepSplitBelow ? 4 : 1;
-    g_fix_per_stretch = plan->max_later_tiles < 96 ? (plan->max_later_tiles > 0 ? plan->max_later_tiles : 1) : 96;
+    {   // groups of 8 tiles for a stretch's first 96 tiles, of 32 beyond
+        const int m = plan->max_later_tiles;
+        g_fix_groups = m <= 96 ? (m + 7) / 8 : 12 + (m - 96 + 31) / 32;
+        if (g_fix_groups < 1) g_fix_groups = 1;
+    }
     g_launches_before_fix = plan->carry_chains ? 3 : 2;
     g_heads = {0, 1, H - 1};
     const size_t nx = (size_t)T * H * P, nb = (size_t)T * G * N, ndt = (size_t)T * H, nst = (size_t)H * P * N;

@@ -98,7 +98,7 @@ def emu_binary(tmp_path_factory):
 @pytest.fixture(scope="session")
 def emu_binary_4waves(tmp_path_factory):
     """The matrix-core scan with 4 waves per workgroup instead of the shipped 12 (32 channels) or 8 (64 channels)."""
-    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4", "-DSSM_SCAN_WAVES_NARROW=4", "-DSSM_FIX_TILES_PER_STRETCH=2"])
+    return _build(tmp_path_factory, "kernel_emu4", os.path.join(CSRC, "scan_mfma.hip"), ["-DSSM_SCAN_WAVES=4", "-DSSM_SCAN_WAVES_NARROW=4", "-DSSM_FIX_FINE_TILES=8"])
 
 
 @pytest.fixture(scope="session")
@@ -200,6 +200,9 @@ CASES = {
     "p32_groups": ((4, 32, 128, 2, 32), 2, dict(batch=2, len_range=(20, 120))),
     # seven heads per group: the four workgroups per (tile, group) of the kernel in front of the scan share them 1, 2, 2, 2
     "heads7": ((7, 32, 128, 1, 64), 2, dict(batch=2, len_range=(40, 150))),
+    # one head, 21 tiles: cut in two, the second stretch is longer than the 8 tiles that the small build of the
+    # second kernel gives workgroups of their own, so its coarse groups get the rest
+    "long2": ((1, 64, 128, 1, 64), 4, dict(seqlen=1300, ckpt_every=500)),
     # four slices per head, large chunk
     "p128": ((1, 128, 128, 1, 256), 4, dict(seqlen=200, ckpt_every=64)),
     # shapes outside the matrix-core path (any storage type takes the fp32 vector kernel)
@@ -428,10 +431,10 @@ def test_emulated_scan_of_sequences_cut_into_stretches_matches_oracle(emu_binary
     _check_case(emu_binary, tmp_path, "bf16", case, split=split)
 
 
-@pytest.mark.parametrize("case", ["ragged", "long"])
-def test_emulated_stretches_with_one_workgroup_for_many_tiles(emu_binary_4waves, tmp_path, case):
-    """As above, built so that a stretch gets at most two workgroups in the second kernel: the last one walks on
-    through the remaining tiles."""
+@pytest.mark.parametrize("case", ["ragged", "long2"])
+def test_emulated_stretches_with_coarse_groups_in_the_second_kernel(emu_binary_4waves, tmp_path, case):
+    """As above, built so that only the first 8 tiles of a stretch get the second kernel's small workgroups (96 in
+    the shipped build): the tiles beyond them go to the workgroups of 32 tiles, eight per wave."""
     _check_case(emu_binary_4waves, tmp_path, "bf16", case, split="2:1")
 
 
